@@ -1,0 +1,169 @@
+/*
+ * turborag.h - C ABI of the MI355X (gfx950) TurboRAG online-prefill library.
+ *
+ * The library implements the data-parallel hot path of TurboRAG (arXiv 2410.07590):
+ *   Sec. 3.4 step 5  contextual KV-cache formation  -> tr_plan, tr_kv_assemble[_batched], tr_kv_append[_batched]
+ *   Sec. 3.4 step 6  KV-cache prefill of the query   -> tr_prefill_attn[_batched]
+ *   Sec. 3.4 step 2  offline document prefill (attention part, independent attention of Sec. 3.2)
+ *                                                     -> tr_chunk_prefill_attn
+ *
+ * Conventions (all entry points):
+ *   - Tensors are token-major, contiguous: [rows, heads, head_dim], element type `tr_shape.dtype`
+ *     (TR_BF16: bfloat16 bit patterns; TR_F32: IEEE float).  Tensor pointers are DEVICE pointers owned by
+ *     the caller; the library never frees them and keeps none past the call, except that a tr_store
+ *     records (does not copy) the two store base pointers.
+ *   - Small index arrays marked "host" are HOST pointers, consumed before the call returns.
+ *     Arrays marked "device" are device pointers read by the kernels.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All GPU work is enqueued on
+ *     it; no call synchronises.  Arguments are validated on the host before anything is enqueued; on error
+ *     nothing has been enqueued.
+ *   - Every function returns a tr_status (0 = TR_OK, negative = error).  tr_last_error() returns a
+ *     thread-local message for the last error on the calling thread.  Nothing throws, aborts or prints.
+ *   - Results are deterministic: same inputs, same bits (no atomics in any reduction).
+ *   - RoPE follows Eq. 3: pair m = channels (2m, 2m+1) of a head is turned by pos * theta_m,
+ *     theta_m = rope_base^(-2m/head_dim).  Only TR_ROPE_INTERLEAVED (the layout Eq. 3 prints) is
+ *     implemented; TR_ROPE_HALF returns TR_ERR_UNSUPPORTED.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Supported shapes: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads; row counts below 2^31.
+ */
+#ifndef TURBORAG_H
+#define TURBORAG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TR_OK = 0,
+    TR_ERR_INVALID_ARG = -1,  /* null pointer, negative count, inconsistent lengths */
+    TR_ERR_BAD_CHUNK_ID = -2, /* chunk id outside [0, n_chunks) of the store */
+    TR_ERR_BAD_PLAN = -3,     /* offsets are not the prefix sum of the chunk lengths, or exceed capacity */
+    TR_ERR_SHAPE = -4,        /* unsupported head_dim / head counts / dtype */
+    TR_ERR_UNSUPPORTED = -5,  /* valid request the library does not implement */
+    TR_ERR_HIP = -6,          /* a HIP runtime call failed (message holds hipGetErrorString) */
+    TR_ERR_WORKSPACE = -7     /* workspace missing, misaligned or too small */
+} tr_status;
+
+typedef enum { TR_POS_COMPOSITE = 0, TR_POS_REORDERED = 1 } tr_pos_mode; /* Sec. 3.2 */
+typedef enum { TR_F32 = 0, TR_BF16 = 1 } tr_dtype;
+typedef enum { TR_ROPE_INTERLEAVED = 0, TR_ROPE_HALF = 1 } tr_rope_layout;
+
+typedef struct tr_shape {
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t dtype;       /* tr_dtype */
+    double rope_base;    /* 10000 in the paper's Eq. 3; a parameter here */
+    int32_t rope_layout; /* tr_rope_layout */
+    int32_t reserved;    /* must be 0 */
+} tr_shape;
+
+typedef struct tr_store tr_store; /* opaque: the per-chunk KV database of Sec. 3.4 step 2, device resident */
+
+/* Message for the last error returned on this thread ("" if none).  Never NULL. */
+const char* tr_last_error(void);
+
+/* ---- the chunk KV store ---------------------------------------------------------------------------------
+ * k_store, v_store: device [store_rows, n_kv_heads, head_dim].  Keys are stored ALREADY ROTATED at their
+ * chunk-local positions 0..len-1 (what the offline prefill of Sec. 3.4 step 2 writes; see
+ * tr_chunk_prefill_attn's k_rot_out).  chunk_row_start: host [n_chunks+1], non-decreasing, chunk c owns rows
+ * [chunk_row_start[c], chunk_row_start[c+1]) (empty chunks allowed).  The table is copied; the two device
+ * pointers are recorded, not copied, and must outlive the store.  No GPU work.
+ * Errors: TR_ERR_INVALID_ARG, TR_ERR_SHAPE, TR_ERR_UNSUPPORTED (rope layout). */
+int tr_store_create(const tr_shape* shape, const void* k_store, const void* v_store,
+                    const int64_t* chunk_row_start, int32_t n_chunks, tr_store** out);
+int tr_store_destroy(tr_store* store);
+
+/* ---- gather plan and position ids (Sec. 3.2) ----------------------------------------------------------------
+ * Host only.  For the retrieved ids in order: offsets[i] = total length of the chunks before i,
+ * offsets[n] = n_doc.  pos_ids (optional, may be NULL): the RoPE position id of every assembled document
+ * row - composite: the chunk-local index t; reordered: offsets[i] + t.  pos_capacity = entries available in
+ * pos_ids.  Errors: TR_ERR_BAD_CHUNK_ID; TR_ERR_BAD_PLAN if n_doc > pos_capacity (pos_ids non-NULL) or
+ * n_doc >= 2^31. */
+int tr_plan(const tr_store* store, const int32_t* chunk_ids /*host [n]*/, int32_t n, int32_t pos_mode,
+            int64_t* offsets /*host out [n+1]*/, int32_t* pos_ids /*host out [n_doc] or NULL*/,
+            int64_t pos_capacity);
+
+/* ---- contextual KV-cache formation (Sec. 3.4 step 5; Sec. 3.2) --------------------------------------------
+ * out_k/out_v: device [out_capacity_rows, n_kv_heads, head_dim].  Rows [offsets[i], offsets[i+1]) receive
+ * chunk chunk_ids[i]:  out_v <- V (copy, both modes);
+ *   composite:  out_k <- K' (copy: keys keep their chunk-local positions);
+ *   reordered:  out_k <- R(offsets[i]) K' (Eq. 3 rotation by the chunk's offset, so the key stored at local
+ *               position t ends at global position offsets[i]+t; computed in fp64, rounded once).
+ * offsets: host [n_chunks+1]; must equal the plan tr_plan returns (exclusive prefix sum of the chunk
+ * lengths), else TR_ERR_BAD_PLAN; offsets[n_chunks] must be <= out_capacity_rows.  Duplicated ids are legal.
+ * n_chunks == 0 is a no-op.  One pass: every byte is read once and written once. */
+int tr_kv_assemble(const tr_store* store, const int32_t* chunk_ids /*host*/, const int64_t* offsets /*host*/,
+                   int32_t n_chunks, int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows,
+                   void* stream);
+
+/* Batched form: request r retrieves chunk_ids[cu_chunks[r] .. cu_chunks[r+1]) and owns cache rows
+ * [cache_row_start[r], cache_row_start[r+1]) of out_k/out_v; its documents fill the first n_doc_r rows of
+ * that range (the plan is computed here), with pos_modes[r] per request.  All index arrays are host arrays.
+ * TR_ERR_BAD_PLAN when a request's documents do not fit its row range or the ranges exceed the capacity. */
+int tr_kv_assemble_batched(const tr_store* store, const int32_t* chunk_ids, const int32_t* cu_chunks /*[n_req+1]*/,
+                           const int32_t* pos_modes /*[n_req]*/, const int64_t* cache_row_start /*[n_req+1]*/,
+                           int32_t n_req, void* out_k, void* out_v, int64_t out_capacity_rows, void* stream);
+
+/* Query tokens' own K/V into the cache (the cache holds K' and V of every token, text after Eq. 4):
+ * cache_k[dst_row+i] <- R(q_pos[i]) k_new[i] (fp64, rounded once), cache_v[dst_row+i] <- v_new[i].
+ * k_new/v_new: device [n_q, n_kv_heads, head_dim] raw; q_pos: device int32 [n_q] position ids. */
+int tr_kv_append(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos /*device*/,
+                 int32_t n_q, void* cache_k, void* cache_v, int64_t dst_row, int64_t cache_capacity_rows,
+                 void* stream);
+
+/* Batched form: tokens packed [cu_q[n_req], ...]; request r's n_q_r tokens go to the LAST n_q_r rows of its
+ * cache range [cache_row_start[r], cache_row_start[r+1]). */
+int tr_kv_append_batched(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos /*device*/,
+                         const int32_t* cu_q /*host [n_req+1]*/, const int64_t* cache_row_start /*host [n_req+1]*/,
+                         int32_t n_req, void* cache_k, void* cache_v, int64_t cache_capacity_rows, void* stream);
+
+/* ---- KV-cache prefill of the query (Sec. 3.4 step 6; Eq. 2, Eq. 4) ---------------------------------------
+ * q: device [n_q, n_q_heads, head_dim] RAW queries; they are rotated in the kernel at q_pos (Eq. 3; the ids
+ * differ from the cache row index under composite positions, which is why both q_pos and kv_len are
+ * arguments).  k, v: device [kv_len, n_kv_heads, head_dim], the assembled cache whose last n_q rows are the
+ * query tokens themselves.  Query token i attends cache rows j <= kv_len - n_q + i (all documents, causal
+ * among the query tokens); scores are scaled by 1/sqrt(head_dim); masked keys get zero weight.
+ * out: device [n_q, n_q_heads, head_dim].  TR_BF16: bf16 MFMA with fp32 accumulation and fp32 softmax;
+ * TR_F32: fp32 throughout.
+ * workspace: device scratch of at least tr_prefill_attn_workspace_size() bytes, 256-byte aligned, used for
+ * split-KV partial results; its contents are undefined afterwards.  n_q == 0 is a no-op.
+ * Errors: TR_ERR_INVALID_ARG (kv_len < n_q, null pointers), TR_ERR_SHAPE, TR_ERR_WORKSPACE. */
+size_t tr_prefill_attn_workspace_size(const tr_shape* shape, int32_t n_q, int64_t kv_len);
+int tr_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v,
+                    const int32_t* q_pos /*device*/, int32_t n_q, int64_t kv_len, void* out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Batched form (one launch for many requests): q/out packed over requests by cu_q; request r's cache is rows
+ * [cache_row_start[r], cache_row_start[r+1]) of k/v (kv_len_r = the range length, its last n_q_r rows are
+ * the request's query tokens); q_pos packed like q.  Index arrays are host arrays. */
+size_t tr_prefill_attn_batched_workspace_size(const tr_shape* shape, const int32_t* cu_q,
+                                              const int64_t* cache_row_start, int32_t n_req);
+int tr_prefill_attn_batched(const tr_shape* shape, const void* q, const void* k, const void* v,
+                            const int32_t* q_pos /*device*/, const int32_t* cu_q /*host*/,
+                            const int64_t* cache_row_start /*host*/, int32_t n_req, void* out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- offline document prefill, attention part (Sec. 3.4 step 2; independent attention, Sec. 3.2) ----------
+ * Chunks packed on one token axis: q device [total_tokens, n_q_heads, d], k, v device
+ * [total_tokens, n_kv_heads, d], all RAW; cu_chunk_lens: DEVICE int32 [n_chunks+1], cu[0] = 0,
+ * cu[n_chunks] = total_tokens, chunk c owns rows [cu[c], cu[c+1]).  Token t of chunk c attends rows
+ * cu[c] .. t of its own chunk only (block-diagonal causal mask); q and k are rotated at the chunk-local
+ * position t - cu[c] (Eq. 3).  out: device [total_tokens, n_q_heads, d].
+ * k_rot_out: device [total_tokens, n_kv_heads, d], REQUIRED: receives K' = R(t - cu[c]) k (fp64, rounded
+ * once) - the keys the store keeps; it may alias k (in-place).  The attention reads K' from it.
+ * max_chunk_len: an upper bound on the chunk lengths (sizes the position table).
+ * workspace: at least tr_chunk_prefill_attn_workspace_size() bytes, 256-byte aligned. */
+size_t tr_chunk_prefill_attn_workspace_size(const tr_shape* shape, int64_t total_tokens, int32_t max_chunk_len);
+int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v,
+                          const int32_t* cu_chunk_lens /*device*/, int32_t n_chunks, int64_t total_tokens,
+                          int32_t max_chunk_len, void* out, void* k_rot_out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TURBORAG_H */

@@ -1,0 +1,209 @@
+"""ctypes binding of libturborag_hip.so - same names as include/turborag.h, argument marshalling only.
+
+Every step of the hot path runs in the library's HIP kernels.  torch is used for device
+memory and for the current stream handle; nothing here computes.  If the library is missing
+the import fails loudly: there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+TR_OK = 0
+TR_ERR_INVALID_ARG, TR_ERR_BAD_CHUNK_ID, TR_ERR_BAD_PLAN, TR_ERR_SHAPE = -1, -2, -3, -4
+TR_ERR_UNSUPPORTED, TR_ERR_HIP, TR_ERR_WORKSPACE = -5, -6, -7
+TR_POS_COMPOSITE, TR_POS_REORDERED = 0, 1
+TR_F32, TR_BF16 = 0, 1
+TR_ROPE_INTERLEAVED, TR_ROPE_HALF = 0, 1
+
+EXPORTS = [
+    "tr_last_error", "tr_store_create", "tr_store_destroy", "tr_plan",
+    "tr_kv_assemble", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched",
+    "tr_prefill_attn_workspace_size", "tr_prefill_attn",
+    "tr_prefill_attn_batched_workspace_size", "tr_prefill_attn_batched",
+    "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
+]
+
+
+class tr_shape(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32), ("rope_base", C.c_double), ("rope_layout", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class TurboRagError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("tr error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+
+def lib_path():
+    return _build.LIB
+
+
+def lib():
+    """Load the in-tree library (it must have been built: __graft_entry__.build() or `python -m ...build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            raise RuntimeError("libturborag_hip.so is not built; run `python -m paper_2410_07590_amd.build`")
+        L = C.CDLL(_build.LIB)
+        L.tr_last_error.restype = C.c_char_p
+        for name in ("tr_prefill_attn_workspace_size", "tr_prefill_attn_batched_workspace_size",
+                     "tr_chunk_prefill_attn_workspace_size"):
+            getattr(L, name).restype = C.c_size_t
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != TR_OK:
+        raise TurboRagError(rc, lib().tr_last_error().decode())
+
+
+def make_shape(n_q_heads, n_kv_heads, head_dim, dtype, rope_base, rope_layout=TR_ROPE_INTERLEAVED):
+    if isinstance(dtype, str):
+        dtype = {"f32": TR_F32, "bf16": TR_BF16}[dtype]
+    elif isinstance(dtype, torch.dtype):
+        dtype = {torch.float32: TR_F32, torch.bfloat16: TR_BF16}[dtype]
+    return tr_shape(n_q_heads, n_kv_heads, head_dim, dtype, float(rope_base), rope_layout, 0)
+
+
+def _dev(t):
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous"
+    return C.c_void_p(t.data_ptr())
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+class Store:
+    """Owns a tr_store handle; keeps the store tensors alive."""
+
+    def __init__(self, shape, k_store, v_store, chunk_row_start):
+        self.shape, self.k, self.v = shape, k_store, v_store
+        rs, rs_p = _host(chunk_row_start, np.int64)
+        self.row_start = rs
+        self.handle = C.c_void_p(0)
+        _check(lib().tr_store_create(C.byref(shape), _dev(k_store) if k_store is not None else None,
+                                     _dev(v_store) if v_store is not None else None, rs_p,
+                                     C.c_int32(rs.size - 1), C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib().tr_store_destroy(self.handle)
+            self.handle = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def tr_store_create(shape, k_store, v_store, chunk_row_start):
+    return Store(shape, k_store, v_store, chunk_row_start)
+
+
+def tr_plan(store, chunk_ids, pos_mode, want_pos_ids=True):
+    """Returns (offsets int64[n+1], pos_ids int32[n_doc] or None)."""
+    ids, ids_p = _host(chunk_ids, np.int32)
+    offsets = np.zeros(ids.size + 1, np.int64)
+    _check(lib().tr_plan(store.handle, ids_p, C.c_int32(ids.size), C.c_int32(pos_mode),
+                         offsets.ctypes.data_as(C.c_void_p), None, C.c_int64(0)))
+    if not want_pos_ids:
+        return offsets, None
+    pos = np.zeros(int(offsets[-1]), np.int32)
+    _check(lib().tr_plan(store.handle, ids_p, C.c_int32(ids.size), C.c_int32(pos_mode),
+                         offsets.ctypes.data_as(C.c_void_p), pos.ctypes.data_as(C.c_void_p), C.c_int64(pos.size)))
+    return offsets, pos
+
+
+def tr_kv_assemble(store, chunk_ids, offsets, pos_mode, out_k, out_v, stream=None):
+    ids, ids_p = _host(chunk_ids, np.int32)
+    off, off_p = _host(offsets, np.int64)
+    _check(lib().tr_kv_assemble(store.handle, ids_p, off_p, C.c_int32(ids.size), C.c_int32(pos_mode),
+                                _dev(out_k), _dev(out_v), C.c_int64(out_k.shape[0]), _stream(stream)))
+
+
+def tr_kv_assemble_batched(store, chunk_ids, cu_chunks, pos_modes, cache_row_start, out_k, out_v, stream=None):
+    ids, ids_p = _host(chunk_ids, np.int32)
+    cu, cu_p = _host(cu_chunks, np.int32)
+    pm, pm_p = _host(pos_modes, np.int32)
+    rs, rs_p = _host(cache_row_start, np.int64)
+    _check(lib().tr_kv_assemble_batched(store.handle, ids_p, cu_p, pm_p, rs_p, C.c_int32(pm.size),
+                                        _dev(out_k), _dev(out_v), C.c_int64(out_k.shape[0]), _stream(stream)))
+
+
+def tr_kv_append(shape, k_new, v_new, q_pos, cache_k, cache_v, dst_row, stream=None):
+    _check(lib().tr_kv_append(C.byref(shape), _dev(k_new), _dev(v_new), _dev(q_pos), C.c_int32(k_new.shape[0]),
+                              _dev(cache_k), _dev(cache_v), C.c_int64(dst_row), C.c_int64(cache_k.shape[0]),
+                              _stream(stream)))
+
+
+def tr_kv_append_batched(shape, k_new, v_new, q_pos, cu_q, cache_row_start, cache_k, cache_v, stream=None):
+    cu, cu_p = _host(cu_q, np.int32)
+    rs, rs_p = _host(cache_row_start, np.int64)
+    _check(lib().tr_kv_append_batched(C.byref(shape), _dev(k_new), _dev(v_new), _dev(q_pos), cu_p, rs_p,
+                                      C.c_int32(cu.size - 1), _dev(cache_k), _dev(cache_v),
+                                      C.c_int64(cache_k.shape[0]), _stream(stream)))
+
+
+def tr_prefill_attn_workspace_size(shape, n_q, kv_len):
+    return int(lib().tr_prefill_attn_workspace_size(C.byref(shape), C.c_int32(n_q), C.c_int64(kv_len)))
+
+
+def tr_prefill_attn(shape, q, k, v, q_pos, kv_len, out, workspace=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().tr_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), C.c_int32(q.shape[0]),
+                                 C.c_int64(kv_len), _dev(out), _dev(workspace), C.c_size_t(ws_bytes), _stream(stream)))
+
+
+def tr_prefill_attn_batched_workspace_size(shape, cu_q, cache_row_start):
+    cu, cu_p = _host(cu_q, np.int32)
+    rs, rs_p = _host(cache_row_start, np.int64)
+    return int(lib().tr_prefill_attn_batched_workspace_size(C.byref(shape), cu_p, rs_p, C.c_int32(cu.size - 1)))
+
+
+def tr_prefill_attn_batched(shape, q, k, v, q_pos, cu_q, cache_row_start, out, workspace=None, stream=None):
+    cu, cu_p = _host(cu_q, np.int32)
+    rs, rs_p = _host(cache_row_start, np.int64)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().tr_prefill_attn_batched(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), cu_p, rs_p,
+                                         C.c_int32(cu.size - 1), _dev(out), _dev(workspace), C.c_size_t(ws_bytes),
+                                         _stream(stream)))
+
+
+def tr_chunk_prefill_attn_workspace_size(shape, total_tokens, max_chunk_len):
+    return int(lib().tr_chunk_prefill_attn_workspace_size(C.byref(shape), C.c_int64(total_tokens), C.c_int32(max_chunk_len)))
+
+
+def tr_chunk_prefill_attn(shape, q, k, v, cu_chunk_lens, n_chunks, max_chunk_len, out, k_rot_out, workspace, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().tr_chunk_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(cu_chunk_lens),
+                                       C.c_int32(n_chunks), C.c_int64(q.shape[0]), C.c_int32(max_chunk_len),
+                                       _dev(out), _dev(k_rot_out), _dev(workspace), C.c_size_t(ws_bytes),
+                                       _stream(stream)))
+
+
+def workspace(nbytes, device="cuda"):
+    """A 256-byte aligned device scratch tensor (torch's allocator aligns to at least 512 bytes)."""
+    t = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    assert t.data_ptr() % 256 == 0
+    return t

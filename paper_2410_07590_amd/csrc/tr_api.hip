@@ -1,0 +1,525 @@
+// Host side of the C ABI: argument validation, gather plans, launch geometry.  No kernels here.
+#include "tr_internal.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <new>
+
+// ---- errors ---------------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+int tr_fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+void tr_clear_error() { g_err[0] = 0; }
+
+extern "C" const char* tr_last_error(void) { return g_err; }
+
+int tr_check_shape(const tr_shape* s)
+{
+    if (!s) return tr_fail(TR_ERR_INVALID_ARG, "shape is NULL");
+    if (s->dtype != TR_F32 && s->dtype != TR_BF16) return tr_fail(TR_ERR_SHAPE, "dtype %d is not TR_F32/TR_BF16", s->dtype);
+    if (s->head_dim != 64 && s->head_dim != 128) return tr_fail(TR_ERR_SHAPE, "head_dim %d: only 64 and 128 are supported", s->head_dim);
+    if (s->n_kv_heads < 1 || s->n_q_heads < 1 || s->n_q_heads % s->n_kv_heads != 0)
+        return tr_fail(TR_ERR_SHAPE, "n_q_heads %d must be a positive multiple of n_kv_heads %d", s->n_q_heads, s->n_kv_heads);
+    if (s->n_q_heads / s->n_kv_heads > 128) return tr_fail(TR_ERR_SHAPE, "group size above 128");
+    if (!(s->rope_base > 1.0) || !isfinite(s->rope_base)) return tr_fail(TR_ERR_SHAPE, "rope_base must be finite and > 1");
+    if (s->rope_layout == TR_ROPE_HALF) return tr_fail(TR_ERR_UNSUPPORTED, "TR_ROPE_HALF is not implemented (Eq. 3 pairs adjacent channels)");
+    if (s->rope_layout != TR_ROPE_INTERLEAVED) return tr_fail(TR_ERR_INVALID_ARG, "rope_layout %d", s->rope_layout);
+    if (s->reserved != 0) return tr_fail(TR_ERR_INVALID_ARG, "reserved must be 0");
+    return TR_OK;
+}
+
+void tr_fill_theta(const tr_shape* s, double* theta)
+{
+    for (int m = 0; m < 64; ++m) theta[m] = 0.0;
+    for (int m = 0; m < s->head_dim / 2; ++m) theta[m] = pow(s->rope_base, -2.0 * (double)m / (double)s->head_dim);
+}
+
+static const int64_t ROW_LIMIT = ((int64_t)1 << 31) - 1;
+
+// ---- store ----------------------------------------------------------------------------------------------------
+extern "C" int tr_store_create(const tr_shape* shape, const void* k_store, const void* v_store,
+                               const int64_t* chunk_row_start, int32_t n_chunks, tr_store** out)
+{
+    tr_clear_error();
+    if (!out) return tr_fail(TR_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    if (n_chunks < 0 || !chunk_row_start) return tr_fail(TR_ERR_INVALID_ARG, "chunk_row_start NULL or n_chunks < 0");
+    if (chunk_row_start[0] < 0) return tr_fail(TR_ERR_INVALID_ARG, "chunk_row_start[0] < 0");
+    for (int c = 0; c < n_chunks; ++c)
+        if (chunk_row_start[c + 1] < chunk_row_start[c]) return tr_fail(TR_ERR_INVALID_ARG, "chunk_row_start decreases at chunk %d", c);
+    if (chunk_row_start[n_chunks] > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "store has 2^31 rows or more");
+    if (chunk_row_start[n_chunks] > 0 && (!k_store || !v_store)) return tr_fail(TR_ERR_INVALID_ARG, "store pointer is NULL");
+    tr_store* st = new (std::nothrow) tr_store;
+    if (!st) return tr_fail(TR_ERR_INVALID_ARG, "out of host memory");
+    st->shape = *shape;
+    st->k = k_store;
+    st->v = v_store;
+    st->row_start.assign(chunk_row_start, chunk_row_start + n_chunks + 1);
+    *out = st;
+    return TR_OK;
+}
+
+extern "C" int tr_store_destroy(tr_store* store)
+{
+    tr_clear_error();
+    delete store;
+    return TR_OK;
+}
+
+// ---- plan (Sec. 3.2) --------------------------------------------------------------------------------------------
+extern "C" int tr_plan(const tr_store* store, const int32_t* chunk_ids, int32_t n, int32_t pos_mode,
+                       int64_t* offsets, int32_t* pos_ids, int64_t pos_capacity)
+{
+    tr_clear_error();
+    if (!store || !offsets || n < 0 || (n > 0 && !chunk_ids)) return tr_fail(TR_ERR_INVALID_ARG, "tr_plan: NULL argument or n < 0");
+    if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
+    const int n_store = (int)store->row_start.size() - 1;
+    int64_t off = 0;
+    for (int i = 0; i < n; ++i) {
+        const int32_t c = chunk_ids[i];
+        if (c < 0 || c >= n_store) return tr_fail(TR_ERR_BAD_CHUNK_ID, "chunk_ids[%d] = %d outside [0, %d)", i, c, n_store);
+        offsets[i] = off;
+        off += store->row_start[c + 1] - store->row_start[c];
+    }
+    offsets[n] = off;
+    if (off > ROW_LIMIT) return tr_fail(TR_ERR_BAD_PLAN, "assembled context has 2^31 rows or more");
+    if (pos_ids) {
+        if (off > pos_capacity) return tr_fail(TR_ERR_BAD_PLAN, "pos_ids holds %lld entries, plan needs %lld", (long long)pos_capacity, (long long)off);
+        for (int i = 0; i < n; ++i) {
+            const int64_t len = offsets[i + 1] - offsets[i];
+            const int64_t first = (pos_mode == TR_POS_REORDERED) ? offsets[i] : 0;
+            for (int64_t t = 0; t < len; ++t) pos_ids[offsets[i] + t] = (int32_t)(first + t);
+        }
+    }
+    return TR_OK;
+}
+
+// ---- KV-cache formation ---------------------------------------------------------------------------------------------
+namespace {
+
+struct CopyRun { int64_t src_row, dst_row, n_rows, delta; };
+
+int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* out_k, void* out_v, hipStream_t stream)
+{
+    const tr_shape* sh = &store->shape;
+    const int eb = tr_elem_bytes(sh);
+    const int row_units = sh->n_kv_heads * sh->head_dim * eb / 16;
+    int64_t total_units = 0;
+    for (const CopyRun& r : runs) total_units += r.n_rows * row_units;
+    if (total_units == 0) return TR_OK;
+    // span: units of K (and V) per block.  Enough blocks to fill 256 CUs several times over, at most 16
+    // units (256 B) of K and V per thread.
+    int64_t span = (total_units + 2047) / 2048;
+    span = ((span + 255) / 256) * 256;
+    if (span < 256) span = 256;
+    if (span > 4096) span = 4096;
+
+    TrAssembleArgs a;
+    memset(&a, 0, sizeof a);
+    a.k_src = store->k;
+    a.v_src = store->v;
+    a.k_dst = out_k;
+    a.v_dst = out_v;
+    a.row_units = row_units;
+    a.head_units = sh->head_dim * eb / 16;
+    a.span_units = (int32_t)span;
+    a.half_dim = sh->head_dim / 2;
+    tr_fill_theta(sh, a.theta);
+    size_t i = 0;
+    while (i < runs.size()) {
+        int n = 0, blocks = 0;
+        while (i < runs.size() && n < TR_MAX_COPY_DESC) {
+            const CopyRun& r = runs[i++];
+            if (r.n_rows == 0) continue;
+            TrCopyDesc& d = a.desc[n++];
+            d.src_row = (int32_t)r.src_row;
+            d.dst_row = (int32_t)r.dst_row;
+            d.n_rows = (int32_t)r.n_rows;
+            d.delta = (int32_t)r.delta;
+            d.blk_start = blocks;
+            blocks += (int)((r.n_rows * row_units + span - 1) / span);
+        }
+        a.n_desc = n;
+        if (n == 0) continue;
+        int rc = tr_launch_assemble(a, sh->dtype, blocks, stream);
+        if (rc) return rc;
+    }
+    return TR_OK;
+}
+
+} // namespace
+
+extern "C" int tr_kv_assemble(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
+                              int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
+{
+    tr_clear_error();
+    if (!store || n_chunks < 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble: store NULL or n_chunks < 0");
+    if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
+    if (n_chunks == 0) return TR_OK;
+    if (!chunk_ids || !offsets) return tr_fail(TR_ERR_INVALID_ARG, "chunk_ids or offsets is NULL");
+    if (out_capacity_rows < 0 || out_capacity_rows > ROW_LIMIT) return tr_fail(TR_ERR_INVALID_ARG, "out_capacity_rows out of range");
+    const int n_store = (int)store->row_start.size() - 1;
+    std::vector<CopyRun> runs;
+    runs.reserve(n_chunks);
+    int64_t off = 0;
+    for (int i = 0; i < n_chunks; ++i) {
+        const int32_t c = chunk_ids[i];
+        if (c < 0 || c >= n_store) return tr_fail(TR_ERR_BAD_CHUNK_ID, "chunk_ids[%d] = %d outside [0, %d)", i, c, n_store);
+        if (offsets[i] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, the prefix sum of the chunk lengths is %lld", i, (long long)offsets[i], (long long)off);
+        const int64_t len = store->row_start[c + 1] - store->row_start[c];
+        runs.push_back({store->row_start[c], off, len, pos_mode == TR_POS_REORDERED ? off : 0});
+        off += len;
+    }
+    if (offsets[n_chunks] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, expected n_doc = %lld", n_chunks, (long long)offsets[n_chunks], (long long)off);
+    if (off > out_capacity_rows) return tr_fail(TR_ERR_BAD_PLAN, "plan needs %lld rows, the cache holds %lld", (long long)off, (long long)out_capacity_rows);
+    if (off > 0 && (!out_k || !out_v)) return tr_fail(TR_ERR_INVALID_ARG, "out_k or out_v is NULL");
+    return launch_runs(store, runs, out_k, out_v, (hipStream_t)stream);
+}
+
+extern "C" int tr_kv_assemble_batched(const tr_store* store, const int32_t* chunk_ids, const int32_t* cu_chunks,
+                                      const int32_t* pos_modes, const int64_t* cache_row_start, int32_t n_req,
+                                      void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
+{
+    tr_clear_error();
+    if (!store || n_req < 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble_batched: store NULL or n_req < 0");
+    if (n_req == 0) return TR_OK;
+    if (!cu_chunks || !pos_modes || !cache_row_start) return tr_fail(TR_ERR_INVALID_ARG, "index array is NULL");
+    if (out_capacity_rows < 0 || out_capacity_rows > ROW_LIMIT) return tr_fail(TR_ERR_INVALID_ARG, "out_capacity_rows out of range");
+    if (cu_chunks[0] != 0 || cache_row_start[0] < 0) return tr_fail(TR_ERR_INVALID_ARG, "cu_chunks[0] must be 0 and cache_row_start[0] >= 0");
+    const int n_store = (int)store->row_start.size() - 1;
+    std::vector<CopyRun> runs;
+    int64_t total = 0;
+    for (int r = 0; r < n_req; ++r) {
+        if (cu_chunks[r + 1] < cu_chunks[r]) return tr_fail(TR_ERR_INVALID_ARG, "cu_chunks decreases at request %d", r);
+        if (cache_row_start[r + 1] < cache_row_start[r]) return tr_fail(TR_ERR_BAD_PLAN, "cache_row_start decreases at request %d", r);
+        if (pos_modes[r] != TR_POS_COMPOSITE && pos_modes[r] != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_modes[%d] = %d", r, pos_modes[r]);
+        if (cu_chunks[r + 1] > cu_chunks[r] && !chunk_ids) return tr_fail(TR_ERR_INVALID_ARG, "chunk_ids is NULL");
+        int64_t off = 0;
+        for (int i = cu_chunks[r]; i < cu_chunks[r + 1]; ++i) {
+            const int32_t c = chunk_ids[i];
+            if (c < 0 || c >= n_store) return tr_fail(TR_ERR_BAD_CHUNK_ID, "chunk_ids[%d] = %d outside [0, %d)", i, c, n_store);
+            const int64_t len = store->row_start[c + 1] - store->row_start[c];
+            runs.push_back({store->row_start[c], cache_row_start[r] + off, len, pos_modes[r] == TR_POS_REORDERED ? off : 0});
+            off += len;
+        }
+        if (off > cache_row_start[r + 1] - cache_row_start[r])
+            return tr_fail(TR_ERR_BAD_PLAN, "request %d: documents need %lld rows, its cache range has %lld", r, (long long)off,
+                           (long long)(cache_row_start[r + 1] - cache_row_start[r]));
+        total += off;
+    }
+    if (cache_row_start[n_req] > out_capacity_rows) return tr_fail(TR_ERR_BAD_PLAN, "cache ranges end at row %lld, the cache holds %lld", (long long)cache_row_start[n_req], (long long)out_capacity_rows);
+    if (total > 0 && (!out_k || !out_v)) return tr_fail(TR_ERR_INVALID_ARG, "out_k or out_v is NULL");
+    return launch_runs(store, runs, out_k, out_v, (hipStream_t)stream);
+}
+
+// ---- query append ---------------------------------------------------------------------------------------------------
+namespace {
+int launch_append(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos,
+                  const std::vector<TrAppendDesc>& descs, void* cache_k, void* cache_v, hipStream_t stream)
+{
+    TrAppendArgs a;
+    memset(&a, 0, sizeof a);
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.q_pos = q_pos;
+    a.cache_k = cache_k;
+    a.cache_v = cache_v;
+    a.n_kv_heads = shape->n_kv_heads;
+    a.head_dim = shape->head_dim;
+    tr_fill_theta(shape, a.theta);
+    size_t i = 0;
+    while (i < descs.size()) {
+        int n = 0, tokens = 0;
+        while (i < descs.size() && n < TR_MAX_APPEND_DESC) {
+            if (descs[i].n_q > 0) { a.desc[n++] = descs[i]; tokens += descs[i].n_q; }
+            ++i;
+        }
+        a.n_desc = n;
+        a.total_tokens = tokens;
+        if (n == 0) continue;
+        int rc = tr_launch_append(a, shape->dtype, stream);
+        if (rc) return rc;
+    }
+    return TR_OK;
+}
+} // namespace
+
+extern "C" int tr_kv_append(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos, int32_t n_q,
+                            void* cache_k, void* cache_v, int64_t dst_row, int64_t cache_capacity_rows, void* stream)
+{
+    tr_clear_error();
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    if (n_q < 0 || dst_row < 0) return tr_fail(TR_ERR_INVALID_ARG, "n_q or dst_row negative");
+    if (n_q == 0) return TR_OK;
+    if (!k_new || !v_new || !q_pos || !cache_k || !cache_v) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_append: NULL pointer");
+    if (cache_capacity_rows > ROW_LIMIT || dst_row + n_q > cache_capacity_rows)
+        return tr_fail(TR_ERR_BAD_PLAN, "rows [%lld, %lld) do not fit a cache of %lld rows", (long long)dst_row, (long long)(dst_row + n_q), (long long)cache_capacity_rows);
+    std::vector<TrAppendDesc> d(1);
+    d[0].q_row0 = 0;
+    d[0].n_q = n_q;
+    d[0].dst_row0 = (int32_t)dst_row;
+    return launch_append(shape, k_new, v_new, q_pos, d, cache_k, cache_v, (hipStream_t)stream);
+}
+
+extern "C" int tr_kv_append_batched(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos,
+                                    const int32_t* cu_q, const int64_t* cache_row_start, int32_t n_req, void* cache_k,
+                                    void* cache_v, int64_t cache_capacity_rows, void* stream)
+{
+    tr_clear_error();
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    if (n_req < 0) return tr_fail(TR_ERR_INVALID_ARG, "n_req < 0");
+    if (n_req == 0) return TR_OK;
+    if (!cu_q || !cache_row_start) return tr_fail(TR_ERR_INVALID_ARG, "index array is NULL");
+    if (cu_q[0] != 0) return tr_fail(TR_ERR_INVALID_ARG, "cu_q[0] must be 0");
+    if (cache_capacity_rows > ROW_LIMIT || cache_row_start[n_req] > cache_capacity_rows || cache_row_start[0] < 0)
+        return tr_fail(TR_ERR_BAD_PLAN, "cache ranges exceed the capacity");
+    std::vector<TrAppendDesc> d;
+    for (int r = 0; r < n_req; ++r) {
+        const int n_q = cu_q[r + 1] - cu_q[r];
+        const int64_t len = cache_row_start[r + 1] - cache_row_start[r];
+        if (n_q < 0 || len < 0) return tr_fail(TR_ERR_INVALID_ARG, "cu_q or cache_row_start decreases at request %d", r);
+        if (n_q > len) return tr_fail(TR_ERR_BAD_PLAN, "request %d: %d query tokens, cache range of %lld rows", r, n_q, (long long)len);
+        TrAppendDesc e;
+        e.q_row0 = cu_q[r];
+        e.n_q = n_q;
+        e.dst_row0 = (int32_t)(cache_row_start[r + 1] - n_q);
+        d.push_back(e);
+    }
+    if (cu_q[n_req] > 0 && (!k_new || !v_new || !q_pos || !cache_k || !cache_v)) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_append_batched: NULL pointer");
+    return launch_append(shape, k_new, v_new, q_pos, d, cache_k, cache_v, (hipStream_t)stream);
+}
+
+// ---- query prefill attention ------------------------------------------------------------------------------------------
+namespace {
+
+struct ReqGeom { int32_t q_row0, n_q; int64_t kv_row0, kv_len; };
+
+constexpr int KEY_TILE = 64;
+constexpr int WG_ROWS_ = 128;
+constexpr int TARGET_ITEMS = 512;   // two 256-thread workgroups per CU on 256 CUs
+constexpr int MIN_SPLIT_KEYS = 256;
+
+// Fills the per-request descriptors of one launch (requests [r0, r1)); returns the partial rows it needs.
+int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t r0, size_t r1, TrPrefixArgs* a,
+                    bool* any_split, int* total_tokens)
+{
+    const int g = sh->n_q_heads / sh->n_kv_heads;
+    const int tpt = WG_ROWS_ / g;
+    int64_t base_items = 0;
+    for (size_t r = r0; r < r1; ++r) base_items += (int64_t)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads;
+    int want_split = 1;
+    if (sh->dtype == TR_BF16 && base_items > 0 && base_items < TARGET_ITEMS) want_split = (int)((TARGET_ITEMS + base_items - 1) / base_items);
+    int items = 0, n = 0, toks = 0;
+    int64_t ws_rows = 0;
+    bool any = false;
+    for (size_t r = r0; r < r1; ++r) {
+        const ReqGeom& q = reqs[r];
+        if (q.n_q == 0) continue;
+        int n_split = want_split;
+        const int64_t max_split = (q.kv_len + MIN_SPLIT_KEYS - 1) / MIN_SPLIT_KEYS;
+        if (n_split > max_split) n_split = (int)max_split;
+        if (n_split < 1) n_split = 1;
+        int64_t split_len = (q.kv_len + n_split - 1) / n_split;
+        split_len = ((split_len + KEY_TILE - 1) / KEY_TILE) * KEY_TILE;
+        n_split = (int)((q.kv_len + split_len - 1) / split_len);
+        if (a) {
+            TrSeqDesc& d = a->seq[n];
+            d.q_row0 = q.q_row0;
+            d.n_q = q.n_q;
+            d.kv_row0 = (int32_t)q.kv_row0;
+            d.kv_len = (int32_t)q.kv_len;
+            d.item0 = items;
+            d.n_tiles = (q.n_q + tpt - 1) / tpt;
+            d.n_split = n_split;
+            d.split_len = (int32_t)split_len;
+            d.ws_row0 = (int32_t)ws_rows;
+            d.pad_ = 0;
+        }
+        ++n;
+        items += ((q.n_q + tpt - 1) / tpt) * sh->n_kv_heads * n_split;
+        toks += q.n_q;
+        if (n_split > 1) {
+            any = true;
+            ws_rows += (int64_t)n_split * q.n_q * sh->n_q_heads;
+        }
+    }
+    if (a) { a->n_seq = n; a->n_items = items; }
+    if (any_split) *any_split = any;
+    if (total_tokens) *total_tokens = toks;
+    return ws_rows;
+}
+
+size_t prefix_ws_bytes(const tr_shape* sh, const std::vector<ReqGeom>& reqs)
+{
+    size_t need = 0;
+    for (size_t r0 = 0; r0 < reqs.size(); r0 += TR_MAX_SEQ) {
+        size_t r1 = r0 + TR_MAX_SEQ < reqs.size() ? r0 + TR_MAX_SEQ : reqs.size();
+        int64_t rows = plan_prefix(sh, reqs, r0, r1, nullptr, nullptr, nullptr);
+        size_t b = tr_align256((size_t)rows * sh->head_dim * 4) + tr_align256((size_t)rows * 8);
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+int run_prefix(const tr_shape* sh, const void* q, const void* k, const void* v, const int32_t* q_pos,
+               const std::vector<ReqGeom>& reqs, void* out, void* ws, size_t ws_bytes, hipStream_t stream)
+{
+    const size_t need = prefix_ws_bytes(sh, reqs);
+    if (need > 0) {
+        if (!ws) return tr_fail(TR_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+        if (((uintptr_t)ws & 255) != 0) return tr_fail(TR_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+        if (ws_bytes < need) return tr_fail(TR_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", ws_bytes, need);
+    }
+    TrPrefixArgs a;
+    memset(&a, 0, sizeof a);
+    a.q = q; a.k = k; a.v = v; a.q_pos = q_pos; a.out = out;
+    a.n_q_heads = sh->n_q_heads;
+    a.n_kv_heads = sh->n_kv_heads;
+    a.group = sh->n_q_heads / sh->n_kv_heads;
+    a.tok_per_tile = WG_ROWS_ / a.group;
+    a.scale = (float)(1.0 / sqrt((double)sh->head_dim));
+    a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)sh->head_dim));
+    tr_fill_theta(sh, a.theta);
+    for (int m = 0; m < 64; ++m) a.theta_rev[m] = a.theta[m] / 6.283185307179586476925;
+    for (size_t r0 = 0; r0 < reqs.size(); r0 += TR_MAX_SEQ) {
+        size_t r1 = r0 + TR_MAX_SEQ < reqs.size() ? r0 + TR_MAX_SEQ : reqs.size();
+        bool any_split = false;
+        int toks = 0;
+        int64_t rows = plan_prefix(sh, reqs, r0, r1, &a, &any_split, &toks);
+        a.ws_o = (float*)ws;
+        a.ws_ml = (float*)((char*)ws + tr_align256((size_t)rows * sh->head_dim * 4));
+        if (a.n_seq == 0) continue;
+        int rc = tr_launch_prefix_attn(a, sh->dtype, sh->head_dim, any_split, toks * sh->n_q_heads, stream);
+        if (rc) return rc;
+    }
+    return TR_OK;
+}
+
+int batched_geom(const int32_t* cu_q, const int64_t* cache_row_start, int32_t n_req, std::vector<ReqGeom>* reqs)
+{
+    if (n_req < 0) return tr_fail(TR_ERR_INVALID_ARG, "n_req < 0");
+    if (n_req > 0 && (!cu_q || !cache_row_start)) return tr_fail(TR_ERR_INVALID_ARG, "index array is NULL");
+    if (n_req > 0 && (cu_q[0] != 0 || cache_row_start[0] < 0)) return tr_fail(TR_ERR_INVALID_ARG, "cu_q[0] must be 0 and cache_row_start[0] >= 0");
+    for (int r = 0; r < n_req; ++r) {
+        const int n_q = cu_q[r + 1] - cu_q[r];
+        const int64_t len = cache_row_start[r + 1] - cache_row_start[r];
+        if (n_q < 0 || len < 0) return tr_fail(TR_ERR_INVALID_ARG, "cu_q or cache_row_start decreases at request %d", r);
+        if (len < n_q) return tr_fail(TR_ERR_INVALID_ARG, "request %d: kv_len %lld < n_q %d", r, (long long)len, n_q);
+        if (cache_row_start[r + 1] > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "cache has 2^31 rows or more");
+        reqs->push_back({cu_q[r], n_q, cache_row_start[r], len});
+    }
+    return TR_OK;
+}
+
+} // namespace
+
+extern "C" size_t tr_prefill_attn_workspace_size(const tr_shape* shape, int32_t n_q, int64_t kv_len)
+{
+    if (tr_check_shape(shape) || n_q <= 0 || kv_len < n_q || kv_len > ROW_LIMIT) return 0;
+    std::vector<ReqGeom> reqs{{0, n_q, 0, kv_len}};
+    return prefix_ws_bytes(shape, reqs);
+}
+
+extern "C" int tr_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* q_pos,
+                               int32_t n_q, int64_t kv_len, void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    tr_clear_error();
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    if (n_q < 0) return tr_fail(TR_ERR_INVALID_ARG, "n_q < 0");
+    if (kv_len < n_q) return tr_fail(TR_ERR_INVALID_ARG, "kv_len %lld < n_q %d: the cache must hold the query tokens", (long long)kv_len, n_q);
+    if (kv_len > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "kv_len of 2^31 or more");
+    if (n_q == 0) return TR_OK;
+    if (!q || !k || !v || !q_pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn: NULL pointer");
+    std::vector<ReqGeom> reqs{{0, n_q, 0, kv_len}};
+    return run_prefix(shape, q, k, v, q_pos, reqs, out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+extern "C" size_t tr_prefill_attn_batched_workspace_size(const tr_shape* shape, const int32_t* cu_q,
+                                                         const int64_t* cache_row_start, int32_t n_req)
+{
+    std::vector<ReqGeom> reqs;
+    if (tr_check_shape(shape) || batched_geom(cu_q, cache_row_start, n_req, &reqs)) return 0;
+    return prefix_ws_bytes(shape, reqs);
+}
+
+extern "C" int tr_prefill_attn_batched(const tr_shape* shape, const void* q, const void* k, const void* v,
+                                       const int32_t* q_pos, const int32_t* cu_q, const int64_t* cache_row_start,
+                                       int32_t n_req, void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    tr_clear_error();
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    std::vector<ReqGeom> reqs;
+    rc = batched_geom(cu_q, cache_row_start, n_req, &reqs);
+    if (rc) return rc;
+    if (n_req == 0 || cu_q[n_req] == 0) return TR_OK;
+    if (!q || !k || !v || !q_pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn_batched: NULL pointer");
+    return run_prefix(shape, q, k, v, q_pos, reqs, out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+// ---- offline chunk prefill --------------------------------------------------------------------------------------------
+extern "C" size_t tr_chunk_prefill_attn_workspace_size(const tr_shape* shape, int64_t total_tokens, int32_t max_chunk_len)
+{
+    if (tr_check_shape(shape) || total_tokens <= 0 || max_chunk_len <= 0) return 0;
+    return tr_align256((size_t)max_chunk_len * (shape->head_dim / 2) * 16) + tr_align256((size_t)total_tokens * 4);
+}
+
+extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v,
+                                     const int32_t* cu_chunk_lens, int32_t n_chunks, int64_t total_tokens,
+                                     int32_t max_chunk_len, void* out, void* k_rot_out, void* workspace,
+                                     size_t workspace_bytes, void* stream)
+{
+    tr_clear_error();
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    if (n_chunks < 0 || total_tokens < 0 || max_chunk_len < 0) return tr_fail(TR_ERR_INVALID_ARG, "negative count");
+    if (total_tokens > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "2^31 tokens or more");
+    if (total_tokens == 0 || n_chunks == 0) return TR_OK;
+    if (max_chunk_len == 0 || max_chunk_len > total_tokens) return tr_fail(TR_ERR_INVALID_ARG, "max_chunk_len %d must be in [1, total_tokens]", max_chunk_len);
+    if (!q || !k || !v || !cu_chunk_lens || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_chunk_prefill_attn: NULL pointer");
+    if (!k_rot_out) return tr_fail(TR_ERR_INVALID_ARG, "k_rot_out is required (it may alias k)");
+    const size_t need = tr_chunk_prefill_attn_workspace_size(shape, total_tokens, max_chunk_len);
+    if (!workspace) return tr_fail(TR_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+    if (((uintptr_t)workspace & 255) != 0) return tr_fail(TR_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (workspace_bytes < need) return tr_fail(TR_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    hipStream_t s = (hipStream_t)stream;
+    double* table = (double*)workspace;
+    int32_t* tok_start = (int32_t*)((char*)workspace + tr_align256((size_t)max_chunk_len * (shape->head_dim / 2) * 16));
+
+    TrBlockDiagArgs a;
+    memset(&a, 0, sizeof a);
+    tr_fill_theta(shape, a.theta);
+    for (int m = 0; m < 64; ++m) a.theta_rev[m] = a.theta[m] / 6.283185307179586476925;
+    rc = tr_launch_rope_table(table, max_chunk_len, shape->head_dim / 2, a.theta, s);
+    if (rc) return rc;
+    rc = tr_launch_rope_rows(k, k_rot_out, cu_chunk_lens, n_chunks, tok_start, table, max_chunk_len, total_tokens, shape, s);
+    if (rc) return rc;
+    a.q = q;
+    a.k = k_rot_out;
+    a.v = v;
+    a.tok_start = tok_start;
+    a.out = out;
+    a.total_tokens = (int32_t)total_tokens;
+    a.n_q_heads = shape->n_q_heads;
+    a.n_kv_heads = shape->n_kv_heads;
+    a.group = shape->n_q_heads / shape->n_kv_heads;
+    a.tok_per_tile = WG_ROWS_ / a.group;
+    a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);
+    a.scale = (float)(1.0 / sqrt((double)shape->head_dim));
+    a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)shape->head_dim));
+    return tr_launch_blockdiag_attn(a, shape->dtype, shape->head_dim, s);
+}

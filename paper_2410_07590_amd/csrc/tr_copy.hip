@@ -1,0 +1,273 @@
+// Bandwidth-bound kernels: KV-cache formation (gather + per-chunk RoPE re-rotation), query append,
+// and the offline key rotation.  All key rotations are computed in fp64 and rounded once to the
+// storage type, so the rotated keys are reproducible to the last bit against an fp64 definition.
+#include "tr_internal.h"
+
+namespace {
+
+// ---- storage helpers ------------------------------------------------------------------------------------
+
+__device__ __forceinline__ double bf16_bits_to_double(uint32_t b16)
+{
+    return (double)__uint_as_float(b16 << 16);
+}
+
+// double -> bf16 with a single rounding (nearest, ties to even): truncate to fp32, fold the discarded
+// bits into a sticky last bit (round to odd), then round the 24-bit significand to 8 bits.
+__device__ __forceinline__ uint32_t double_to_bf16_bits(double y)
+{
+    float f = __double2float_rz(y);
+    uint32_t u = __float_as_uint(f);
+    u |= ((double)f != y) ? 1u : 0u;
+    if (y != y) return 0x7fc0u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// y = R(angle) x on one pair, unfused multiplies and adds (the order Eq. 3 is written in)
+__device__ __forceinline__ void rotate_pair(double xa, double xb, double c, double s, double& ya, double& yb)
+{
+    ya = __dsub_rn(__dmul_rn(xa, c), __dmul_rn(xb, s));
+    yb = __dadd_rn(__dmul_rn(xb, c), __dmul_rn(xa, s));
+}
+
+template <int DTYPE> struct Unit; // one 16-byte unit of a row
+
+template <> struct Unit<TR_BF16> {
+    static constexpr int PAIRS = 4;
+    __device__ static __forceinline__ uint4 rotate(uint4 x, const double* c, const double* s)
+    {
+        uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            double xa = bf16_bits_to_double(w[p] & 0xffffu), xb = bf16_bits_to_double(w[p] >> 16);
+            double ya, yb;
+            rotate_pair(xa, xb, c[p], s[p], ya, yb);
+            w[p] = double_to_bf16_bits(ya) | (double_to_bf16_bits(yb) << 16);
+        }
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+template <> struct Unit<TR_F32> {
+    static constexpr int PAIRS = 2;
+    __device__ static __forceinline__ uint4 rotate(uint4 x, const double* c, const double* s)
+    {
+        uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            double xa = (double)__uint_as_float(w[2 * p]), xb = (double)__uint_as_float(w[2 * p + 1]);
+            double ya, yb;
+            rotate_pair(xa, xb, c[p], s[p], ya, yb);
+            w[2 * p] = __float_as_uint(__double2float_rn(ya));
+            w[2 * p + 1] = __float_as_uint(__double2float_rn(yb));
+        }
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// streaming (read-once) 16-byte load
+__device__ __forceinline__ uint4 ld_stream(const uint4* p)
+{
+    const u32x4 r = __builtin_nontemporal_load((const u32x4*)p);
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+// ---- KV-cache formation: Sec. 3.4 step 5 with the reordered-position rotation of Sec. 3.2 -------------------
+// A run of rows is contiguous in the store and in the cache, so a block moves a flat span of 16-byte
+// units.  A thread's unit index modulo the units-per-head never changes while it strides by 256, hence
+// the (cos, sin) of "its" pairs for this chunk's offset are loop constants.
+constexpr int ASM_UNROLL = 4;
+
+template <int DTYPE>
+__global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
+{
+    __shared__ double cs[64][2];
+    const int b = blockIdx.x;
+    int lo = 0, hi = a.n_desc - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (a.desc[mid].blk_start <= b) lo = mid; else hi = mid - 1;
+    }
+    const TrCopyDesc d = a.desc[lo];
+    const int64_t run_units = (int64_t)d.n_rows * a.row_units;
+    const int64_t u0 = (int64_t)(b - d.blk_start) * a.span_units;
+    int64_t u1 = u0 + a.span_units;
+    if (u1 > run_units) u1 = run_units;
+    const int tid = threadIdx.x;
+
+    constexpr int P = Unit<DTYPE>::PAIRS;
+    double c[P], s[P];
+    const bool rot = d.delta != 0;
+    if (rot) {
+        if (tid < a.half_dim) {
+            double sn, cn;
+            sincos((double)d.delta * a.theta[tid], &sn, &cn);
+            cs[tid][0] = cn;
+            cs[tid][1] = sn;
+        }
+        __syncthreads();
+        const int m0 = (int)((u0 + tid) % a.head_units) * P;
+#pragma unroll
+        for (int p = 0; p < P; ++p) { c[p] = cs[m0 + p][0]; s[p] = cs[m0 + p][1]; }
+    }
+
+    const uint4* ks = (const uint4*)a.k_src + (int64_t)d.src_row * a.row_units;
+    const uint4* vs = (const uint4*)a.v_src + (int64_t)d.src_row * a.row_units;
+    uint4* kd = (uint4*)a.k_dst + (int64_t)d.dst_row * a.row_units;
+    uint4* vd = (uint4*)a.v_dst + (int64_t)d.dst_row * a.row_units;
+
+    for (int64_t u = u0 + tid; u < u1; u += 256 * ASM_UNROLL) {
+        uint4 kx[ASM_UNROLL], vx[ASM_UNROLL];
+#pragma unroll
+        for (int i = 0; i < ASM_UNROLL; ++i) {
+            int64_t uu = u + 256 * i;
+            if (uu < u1) { kx[i] = ld_stream(ks + uu); vx[i] = ld_stream(vs + uu); }
+        }
+#pragma unroll
+        for (int i = 0; i < ASM_UNROLL; ++i) {
+            int64_t uu = u + 256 * i;
+            if (uu < u1) {
+                kd[uu] = rot ? Unit<DTYPE>::rotate(kx[i], c, s) : kx[i];
+                vd[uu] = vx[i];
+            }
+        }
+    }
+}
+
+// ---- query append: cache rows of the query tokens (K' rotated at q_pos, V copied) -------------------------
+// One thread per (token, pair m): its angle is shared by all KV heads of the token.
+template <int DTYPE>
+__global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
+{
+    const int half = a.head_dim >> 1;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int tok = (int)(gid / half), m = (int)(gid % half);
+    if (tok >= a.total_tokens) return;
+    // request that owns packed token `tok` of this launch
+    int r = 0, base = 0;
+    while (r + 1 < a.n_desc && tok >= base + a.desc[r].n_q) { base += a.desc[r].n_q; ++r; }
+    const int i = tok - base;
+    const int64_t src_row = (int64_t)a.desc[r].q_row0 + i;
+    const int64_t dst_row = (int64_t)a.desc[r].dst_row0 + i;
+    double sn, cn;
+    sincos((double)a.q_pos[src_row] * a.theta[m], &sn, &cn);
+    for (int h = 0; h < a.n_kv_heads; ++h) {
+        const int64_t so = (src_row * a.n_kv_heads + h) * a.head_dim + 2 * m;
+        const int64_t dn = (dst_row * a.n_kv_heads + h) * a.head_dim + 2 * m;
+        if (DTYPE == TR_BF16) {
+            uint32_t w = *(const uint32_t*)((const uint16_t*)a.k_new + so);
+            double ya, yb;
+            rotate_pair(bf16_bits_to_double(w & 0xffffu), bf16_bits_to_double(w >> 16), cn, sn, ya, yb);
+            *(uint32_t*)((uint16_t*)a.cache_k + dn) = double_to_bf16_bits(ya) | (double_to_bf16_bits(yb) << 16);
+            *(uint32_t*)((uint16_t*)a.cache_v + dn) = *(const uint32_t*)((const uint16_t*)a.v_new + so);
+        } else {
+            float2 w = *(const float2*)((const float*)a.k_new + so);
+            double ya, yb;
+            rotate_pair((double)w.x, (double)w.y, cn, sn, ya, yb);
+            *(float2*)((float*)a.cache_k + dn) = make_float2(__double2float_rn(ya), __double2float_rn(yb));
+            *(float2*)((float*)a.cache_v + dn) = *(const float2*)((const float*)a.v_new + so);
+        }
+    }
+}
+
+// ---- offline key rotation (Sec. 3.4 step 2): K' = R(t - cu[c]) k -------------------------------------------
+// table[pos][m] = (cos, sin)(pos * theta_m) in fp64, positions 0 .. n_pos-1
+struct ThetaArg { double v[64]; };
+__global__ __launch_bounds__(256) void rope_table_kernel(double2* table, int n_pos, int half_dim, const ThetaArg theta_arg)
+{
+    const double* theta = theta_arg.v;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= (int64_t)n_pos * half_dim) return;
+    const int pos = (int)(gid / half_dim), m = (int)(gid % half_dim);
+    double sn, cn;
+    sincos((double)pos * theta[m], &sn, &cn);
+    table[gid] = make_double2(cn, sn);
+}
+
+// One thread per 16-byte unit of a key row.  Also records, per token, the first row of its chunk.
+template <int DTYPE>
+__global__ __launch_bounds__(256) void rope_rows_kernel(const uint4* k, uint4* k_rot, const int32_t* cu, int n_chunks,
+                                                        int32_t* tok_start, const double2* table, int table_rows,
+                                                        int64_t total_tokens, int row_units, int head_units, int half_dim)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total_tokens * row_units) return;
+    const int t = (int)(gid / row_units);
+    const int unit = (int)(gid % row_units);
+    // chunk that owns token t: largest c with cu[c] <= t
+    int lo = 0, hi = n_chunks - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (cu[mid] <= t) lo = mid; else hi = mid - 1;
+    }
+    const int start = cu[lo];
+    if (unit == 0) tok_start[t] = start;
+    int pos = t - start;
+    if (pos > table_rows - 1) pos = table_rows - 1; // caller promised max_chunk_len; never read past the table
+    constexpr int P = Unit<DTYPE>::PAIRS;
+    const int m0 = (unit % head_units) * P;
+    double c[P], s[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        double2 e = table[(int64_t)pos * half_dim + m0 + p];
+        c[p] = e.x;
+        s[p] = e.y;
+    }
+    uint4 x = k[gid];
+    k_rot[gid] = (pos == 0) ? x : Unit<DTYPE>::rotate(x, c, s);
+}
+
+} // namespace
+
+int tr_launch_assemble(const TrAssembleArgs& a, int dtype, int n_blocks, hipStream_t s)
+{
+    if (n_blocks <= 0) return TR_OK;
+    if (dtype == TR_BF16) hipLaunchKernelGGL(assemble_kernel<TR_BF16>, dim3(n_blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(assemble_kernel<TR_F32>, dim3(n_blocks), dim3(256), 0, s, a);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
+}
+
+int tr_launch_append(const TrAppendArgs& a, int dtype, hipStream_t s)
+{
+    int64_t threads = (int64_t)a.total_tokens * (a.head_dim / 2);
+    if (threads <= 0) return TR_OK;
+    int blocks = (int)((threads + 255) / 256);
+    if (dtype == TR_BF16) hipLaunchKernelGGL(append_kernel<TR_BF16>, dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(append_kernel<TR_F32>, dim3(blocks), dim3(256), 0, s, a);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
+}
+
+int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* theta, hipStream_t s)
+{
+    int64_t threads = (int64_t)n_pos * half_dim;
+    if (threads <= 0) return TR_OK;
+    ThetaArg th;
+    for (int m = 0; m < 64; ++m) th.v[m] = theta[m];
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                       (double2*)table, n_pos, half_dim, th);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
+}
+
+int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int32_t* tok_start,
+                        const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s)
+{
+    const int eb = tr_elem_bytes(shape);
+    const int row_units = shape->n_kv_heads * shape->head_dim * eb / 16;
+    const int head_units = shape->head_dim * eb / 16;
+    int64_t threads = total_tokens * row_units;
+    if (threads <= 0) return TR_OK;
+    dim3 grid((unsigned)((threads + 255) / 256));
+    if (shape->dtype == TR_BF16)
+        hipLaunchKernelGGL(rope_rows_kernel<TR_BF16>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu, n_chunks,
+                           tok_start, (const double2*)table, table_rows, total_tokens, row_units, head_units, shape->head_dim / 2);
+    else
+        hipLaunchKernelGGL(rope_rows_kernel<TR_F32>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu, n_chunks,
+                           tok_start, (const double2*)table, table_rows, total_tokens, row_units, head_units, shape->head_dim / 2);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
+}

@@ -1,0 +1,141 @@
+// Internal declarations shared by the translation units of libturborag_hip.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+
+#include "../../include/turborag.h"
+
+// ---- error plumbing -------------------------------------------------------------------------------------
+int tr_fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void tr_clear_error();
+#define TR_HIP(expr)                                                                           \
+    do {                                                                                       \
+        hipError_t e__ = (expr);                                                               \
+        if (e__ != hipSuccess) return tr_fail(TR_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+int tr_check_shape(const tr_shape* s);
+static inline int tr_elem_bytes(const tr_shape* s) { return s->dtype == TR_F32 ? 4 : 2; }
+static inline size_t tr_align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct tr_store {
+    tr_shape shape;
+    const void* k;
+    const void* v;
+    std::vector<int64_t> row_start; // n_chunks + 1
+};
+
+// theta_m = base^(-2m/d) in double (text after Eq. 3)
+void tr_fill_theta(const tr_shape* s, double* theta /*[64]*/);
+
+// ---- kernel argument blocks (passed by value; each stays below 4 KB of kernarg) ------------------------------
+
+// One contiguous run of rows to move: src rows [src_row, src_row+n_rows) -> dst rows [dst_row, ...),
+// keys additionally turned by delta positions (0: plain copy).
+struct TrCopyDesc {
+    int32_t src_row;
+    int32_t dst_row;
+    int32_t n_rows;
+    int32_t delta;
+    int32_t blk_start; // first block of the grid that works on this run
+};
+#define TR_MAX_COPY_DESC 128
+struct TrAssembleArgs {
+    const void* k_src;
+    const void* v_src;
+    void* k_dst;
+    void* v_dst;
+    int32_t n_desc;
+    int32_t row_units;  // 16-byte units per row (n_kv_heads * head_dim * elem / 16)
+    int32_t head_units; // 16-byte units per head
+    int32_t span_units; // units of K (and of V) one block moves; multiple of 256
+    int32_t half_dim;   // head_dim / 2
+    int32_t pad_;
+    double theta[64];
+    TrCopyDesc desc[TR_MAX_COPY_DESC];
+};
+
+// append: request r's tokens [q_row0, q_row0+n_q) go to cache rows [dst_row0, dst_row0+n_q)
+struct TrAppendDesc {
+    int32_t q_row0;
+    int32_t n_q;
+    int32_t dst_row0;
+};
+#define TR_MAX_APPEND_DESC 128
+struct TrAppendArgs {
+    const void* k_new;
+    const void* v_new;
+    const int32_t* q_pos;
+    void* cache_k;
+    void* cache_v;
+    int32_t n_desc;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t total_tokens; // tokens covered by this launch (sum of n_q)
+    double theta[64];
+    TrAppendDesc desc[TR_MAX_APPEND_DESC];
+};
+
+// prefix attention: one request
+struct TrSeqDesc {
+    int32_t q_row0;    // first packed query token of the request (row of q / out / q_pos)
+    int32_t n_q;
+    int32_t kv_row0;   // first cache row of the request
+    int32_t kv_len;
+    int32_t item0;     // first work item of the request in this launch
+    int32_t n_tiles;   // row tiles
+    int32_t n_split;   // KV splits (>= 1)
+    int32_t split_len; // keys per split, multiple of the key tile
+    int32_t ws_row0;   // first partial row of the request in the workspace
+    int32_t pad_;
+};
+#define TR_MAX_SEQ 64
+struct TrPrefixArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const int32_t* q_pos;
+    void* out;
+    float* ws_o;  // [partial rows][head_dim] unnormalised outputs
+    float* ws_ml; // [partial rows][2] running max (raw score units) and sum
+    int32_t n_seq;
+    int32_t n_items;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t group;
+    int32_t tok_per_tile;
+    float scale_log2e; // log2(e) / sqrt(head_dim)
+    float scale;       // 1 / sqrt(head_dim)
+    double theta_rev[64]; // theta_m / (2 pi): position * theta_rev = angle in revolutions
+    double theta[64];
+    TrSeqDesc seq[TR_MAX_SEQ];
+};
+
+struct TrBlockDiagArgs {
+    const void* q;
+    const void* k; // rotated keys K'
+    const void* v;
+    const int32_t* tok_start; // [T] first row of the chunk that owns each token
+    void* out;
+    int32_t total_tokens;
+    int32_t n_tiles;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t group;
+    int32_t tok_per_tile;
+    float scale_log2e;
+    float scale;
+    double theta_rev[64];
+    double theta[64];
+};
+
+// ---- launchers implemented in the .hip files --------------------------------------------------------------
+int tr_launch_assemble(const TrAssembleArgs& a, int dtype, int n_blocks, hipStream_t s);
+int tr_launch_append(const TrAppendArgs& a, int dtype, hipStream_t s);
+int tr_launch_prefix_attn(const TrPrefixArgs& a, int dtype, int head_dim, bool any_split, int total_rows, hipStream_t s);
+int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* theta, hipStream_t s);
+int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int32_t* tok_start,
+                        const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s);
+int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int dtype, int head_dim, hipStream_t s);

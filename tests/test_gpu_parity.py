@@ -1,0 +1,272 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bit-exact for plans, position ids and every cache byte; max abs error <= 1e-4 (fp32) / 2e-2 (bf16
+storage, fp32 accumulation) for attention outputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2410_07590_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2410_07590_amd import binding
+    binding.lib()
+    return binding
+
+
+def _store_dev(B, sh, store):
+    return B.Store(H.gpu_shape(B, sh), store.k.cuda(), store.v.cuda(), store.row_start)
+
+
+# ---- configuration 1: tiny fp32, both position modes -------------------------------------------------------
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+def test_config1_fp32(B, mode):
+    cfg = synth.CONFIGS[1]
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    req = synth.make_requests(cfg, store, pos_mode=mode)[0]
+    err, n_bad = H.check_request(B, cfg.shape, store, sd, req, k_mismatch_frac=1e-4)
+    print("config1 mode %d: max abs err %.3e, K mismatches %d" % (mode, err, n_bad))
+
+
+# ---- small ragged bf16 cases: several tiles, ragged tails, empty chunk, duplicate id ----------------------------
+RAGGED = [
+    # (n_q_heads, n_kv_heads, head_dim, base, chunk lens, ids, n_q)
+    (28, 4, 128, 1e6, (37, 64, 129, 0, 200, 1), (2, 0, 3, 4, 1, 0), 19),
+    (32, 8, 128, 5e5, (300, 17, 255), (1, 2, 0), 70),
+    (8, 8, 128, 1e4, (100, 90), (0, 1), 33),          # MHA, group size 1
+    (16, 2, 64, 1e4, (130, 61, 77), (2, 1, 0, 2), 5), # head_dim 64, group size 8
+    (28, 4, 128, 1e6, (64, 64), (0, 1), 1),           # single query token
+]
+
+
+@pytest.mark.parametrize("case", range(len(RAGGED)))
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+def test_ragged_bf16(B, case, mode):
+    hq, hkv, d, base, lens, ids, n_q = RAGGED[case]
+    sh = synth.Shape(hq, hkv, d, "bf16", base)
+    rng = np.random.Generator(np.random.PCG64([99, case]))
+    row_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rows = int(row_start[-1])
+    store = synth.Store(synth.normal_tensor(rng, (rows, hkv, d), sh.torch_dtype),
+                        synth.normal_tensor(rng, (rows, hkv, d), sh.torch_dtype), row_start)
+    sd = _store_dev(B, sh, store)
+    sel = [lens[c] for c in ids]
+    q_pos = (synth.query_start(mode, sel) + np.arange(n_q)).astype(np.int32)
+    req = synth.Request(np.asarray(ids, np.int32), mode, n_q,
+                        synth.normal_tensor(rng, (n_q, hq, d), sh.torch_dtype),
+                        synth.normal_tensor(rng, (n_q, hkv, d), sh.torch_dtype),
+                        synth.normal_tensor(rng, (n_q, hkv, d), sh.torch_dtype), q_pos, sum(sel), sel)
+    err, n_bad = H.check_request(B, sh, store, sd, req)
+    print("ragged %d mode %d: max abs err %.3e" % (case, mode, err))
+
+
+def test_no_documents_and_noops(B):
+    # kv_len == n_q: the query attends only to itself (plain causal); n_chunks == 0 and n_q == 0 are no-ops
+    sh = synth.Shape(8, 2, 128, "bf16", 1e4)
+    rng = np.random.Generator(np.random.PCG64(5))
+    store = synth.Store(synth.normal_tensor(rng, (10, 2, 128), sh.torch_dtype),
+                        synth.normal_tensor(rng, (10, 2, 128), sh.torch_dtype), np.array([0, 10], np.int64))
+    sd = _store_dev(B, sh, store)
+    n_q = 40
+    req = synth.Request(np.zeros(0, np.int32), synth.POS_REORDERED, n_q,
+                        synth.normal_tensor(rng, (n_q, 8, 128), sh.torch_dtype),
+                        synth.normal_tensor(rng, (n_q, 2, 128), sh.torch_dtype),
+                        synth.normal_tensor(rng, (n_q, 2, 128), sh.torch_dtype), np.arange(n_q, dtype=np.int32), 0, [])
+    H.check_request(B, sh, store, sd, req)
+    req0 = synth.Request(np.array([0], np.int32), synth.POS_COMPOSITE, 0,
+                         torch.zeros((0, 8, 128), dtype=sh.torch_dtype), torch.zeros((0, 2, 128), dtype=sh.torch_dtype),
+                         torch.zeros((0, 2, 128), dtype=sh.torch_dtype), np.zeros(0, np.int32), 10, [10])
+    g = H.run_request_gpu(B, sh, sd, req0)
+    assert torch.equal(g["cache_k"].view(torch.uint16), store.k.view(torch.uint16))
+
+
+# ---- configurations 2 and 4 at full size -----------------------------------------------------------------------
+def test_config2_full(B):
+    cfg = synth.CONFIGS[2]
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    req = synth.make_requests(cfg, store)[0]
+    err, n_bad = H.check_request(B, cfg.shape, store, sd, req)
+    print("config2: max abs err %.3e, K one-ulp mismatches %d" % (err, n_bad))
+
+
+def test_config4_full_sampled_rows(B):
+    cfg = synth.CONFIGS[4]
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    req = synth.make_requests(cfg, store)[0]
+    rows = np.array([0, 1, 31, 32, 100, 127, 128, 200, 254, 255], np.int32)   # tile edges and interior
+    err, n_bad = H.check_request(B, cfg.shape, store, sd, req, rows=rows)
+    print("config4: max abs err %.3e on %d sampled query tokens, K one-ulp mismatches %d" % (err, rows.size, n_bad))
+
+
+# ---- configuration 3: batched serving, mixed modes ---------------------------------------------------------------
+def _run_batched(B, cfg, store, sd, reqs):
+    sh = cfg.shape
+    gs = sd.shape
+    n_req = len(reqs)
+    ids = np.concatenate([r.chunk_ids for r in reqs]).astype(np.int32)
+    cu_chunks = np.concatenate([[0], np.cumsum([r.chunk_ids.size for r in reqs])]).astype(np.int32)
+    modes = np.array([r.pos_mode for r in reqs], np.int32)
+    kv_lens = [r.n_doc + r.n_q for r in reqs]
+    cache_row_start = np.concatenate([[0], np.cumsum(kv_lens)]).astype(np.int64)
+    cu_q = np.concatenate([[0], np.cumsum([r.n_q for r in reqs])]).astype(np.int32)
+    total = int(cache_row_start[-1])
+    dt = sh.torch_dtype
+    cache_k = torch.full((total, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=dt, device="cuda")
+    cache_v = torch.full_like(cache_k, float("nan"))
+    q = torch.cat([r.q for r in reqs]).cuda()
+    k_q = torch.cat([r.k_q for r in reqs]).cuda()
+    v_q = torch.cat([r.v_q for r in reqs]).cuda()
+    q_pos = torch.from_numpy(np.concatenate([r.q_pos for r in reqs]).astype(np.int32)).cuda()
+    out = torch.full(q.shape, float("nan"), dtype=dt, device="cuda")
+    B.tr_kv_assemble_batched(sd, ids, cu_chunks, modes, cache_row_start, cache_k, cache_v)
+    B.tr_kv_append_batched(gs, k_q, v_q, q_pos, cu_q, cache_row_start, cache_k, cache_v)
+    ws = B.workspace(B.tr_prefill_attn_batched_workspace_size(gs, cu_q, cache_row_start))
+    B.tr_prefill_attn_batched(gs, q, cache_k, cache_v, q_pos, cu_q, cache_row_start, out, ws)
+    torch.cuda.synchronize()
+    return cache_k.cpu(), cache_v.cpu(), out.cpu(), cache_row_start, cu_q
+
+
+def _check_batched(B, cfg, store, sd, reqs, rows_per_req=None):
+    sh = cfg.shape
+    ck, cv, out, crs, cu_q = _run_batched(B, cfg, store, sd, reqs)
+    worst = 0.0
+    for r, req in enumerate(reqs):
+        rows = None
+        if rows_per_req is not None and req.n_q > rows_per_req:
+            rows = np.unique(np.linspace(0, req.n_q - 1, rows_per_req).astype(np.int32))
+        o = H.run_request_oracle(sh, store, req, rows)
+        s, e = int(crs[r]), int(crs[r + 1])
+        H.assert_same_bits(H.bits(cv[s:e]), o["v_cache_st"], "request %d V" % r)
+        H.assert_same_bits(H.bits(ck[s:e]), o["k_cache_st"], "request %d K" % r, 1e-5)
+        got = H.to_f64(out[cu_q[r]:cu_q[r + 1]])
+        if rows is not None:
+            got = got[rows]
+        assert np.isfinite(got).all()
+        worst = max(worst, float(np.abs(got - o["out"]).max()))
+    assert worst <= H.tol_for(sh), "batched attention max abs err %.3e" % worst
+    return worst
+
+
+def test_config3_scaled_down_batched(B):
+    # same recipe as configuration 3 at a size the oracle does in full: 5 requests x 3 chunks of 20..90 rows
+    cfg = synth.scaled(synth.CONFIGS[3], store_chunks=40, chunk_len_lo=20, chunk_len_hi=90, n_requests=5,
+                       chunks_per_request=3, n_q_lo=3, n_q_hi=40)
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    reqs = synth.make_requests(cfg, store)
+    assert len({r.pos_mode for r in reqs}) == 2 or len(reqs) < 2
+    print("config3 scaled: max abs err %.3e" % _check_batched(B, cfg, store, sd, reqs))
+
+
+def test_config3_full_batched(B):
+    cfg = synth.CONFIGS[3]
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    reqs = synth.make_requests(cfg, store)
+    print("config3: max abs err %.3e (4 sampled query tokens per request)" % _check_batched(B, cfg, store, sd, reqs, rows_per_req=4))
+
+
+# ---- configuration 5: offline chunk prefill ------------------------------------------------------------------------
+def _run_offline(B, sh, pc):
+    gs = H.gpu_shape(B, sh)
+    T = pc.q.shape[0]
+    cu = torch.from_numpy(pc.cu).cuda()
+    max_len = int(np.diff(pc.cu).max())
+    out = torch.full(pc.q.shape, float("nan"), dtype=sh.torch_dtype, device="cuda")
+    k_rot = torch.full(pc.k.shape, float("nan"), dtype=sh.torch_dtype, device="cuda")
+    ws = B.workspace(B.tr_chunk_prefill_attn_workspace_size(gs, T, max_len))
+    B.tr_chunk_prefill_attn(gs, pc.q.cuda(), pc.k.cuda(), pc.v.cuda(), cu, pc.cu.size - 1, max_len, out, k_rot, ws)
+    torch.cuda.synchronize()
+    return out.cpu(), k_rot.cpu()
+
+
+def _check_offline(B, sh, pc, rows=None):
+    out, k_rot = _run_offline(B, sh, pc)
+    o = oracle.offline_chunk_prefill(H.bits(pc.q), H.bits(pc.k), H.bits(pc.v), pc.cu, sh.rope_base, rows=rows)
+    n_bad = H.assert_same_bits(H.bits(k_rot), o["k_rot_st"], "rotated keys K'", 1e-5)
+    got = H.to_f64(out)
+    if rows is not None:
+        got = got[np.asarray(rows)]
+    assert np.isfinite(got).all()
+    err = float(np.abs(got - o["out"]).max())
+    assert err <= H.tol_for(sh), "offline attention max abs err %.3e" % err
+    return err, n_bad
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_offline_ragged_chunks(B, dtype):
+    lens = (70, 1, 129, 33, 64, 200, 5)
+    hq, hkv, d = (32, 8, 128) if dtype == "bf16" else (4, 4, 64)
+    sh = synth.Shape(hq, hkv, d, dtype, 5e5)
+    rng = np.random.Generator(np.random.PCG64(77))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    pc = synth.PackedChunks(synth.normal_tensor(rng, (T, hq, d), sh.torch_dtype), synth.normal_tensor(rng, (T, hkv, d), sh.torch_dtype),
+                            synth.normal_tensor(rng, (T, hkv, d), sh.torch_dtype), cu)
+    err, n_bad = _check_offline(B, sh, pc)
+    print("offline ragged %s: max abs err %.3e" % (dtype, err))
+
+
+def test_offline_group7_head64(B):
+    lens = (90, 40)
+    sh = synth.Shape(14, 2, 64, "bf16", 1e6)
+    rng = np.random.Generator(np.random.PCG64(78))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    pc = synth.PackedChunks(synth.normal_tensor(rng, (T, 14, 64), sh.torch_dtype), synth.normal_tensor(rng, (T, 2, 64), sh.torch_dtype),
+                            synth.normal_tensor(rng, (T, 2, 64), sh.torch_dtype), cu)
+    _check_offline(B, sh, pc)
+
+
+def test_config5_full_sampled_rows(B):
+    cfg = synth.CONFIGS[5]
+    pc = synth.make_packed_chunks(cfg)
+    # first, second, tile-edge and last tokens of a few chunks
+    rows = []
+    for c in (0, 1, 31, 63):
+        s = int(pc.cu[c])
+        rows += [s, s + 1, s + 31, s + 32, s + 63, s + 64, s + 300, s + 511]
+    rows = np.array(sorted(set(rows)), np.int32)
+    err, n_bad = _check_offline(B, cfg.shape, pc, rows)
+    print("config5: max abs err %.3e on %d sampled tokens, K' one-ulp mismatches %d" % (err, rows.size, n_bad))
+
+
+def test_offline_store_feeds_online_path(B):
+    """The keys the offline kernel writes (K') are what the online path assembles: build the store on the GPU
+    with tr_chunk_prefill_attn and check the online output against the oracle run from the RAW keys rotated
+    once at their global positions (Sec. 3.2's equivalence, through the GPU)."""
+    sh = synth.Shape(28, 4, 128, "bf16", 1e6)
+    lens = (100, 64, 150)
+    rng = np.random.Generator(np.random.PCG64(79))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    pc = synth.PackedChunks(synth.normal_tensor(rng, (T, 28, 128), sh.torch_dtype), synth.normal_tensor(rng, (T, 4, 128), sh.torch_dtype),
+                            synth.normal_tensor(rng, (T, 4, 128), sh.torch_dtype), cu)
+    _, k_rot = _run_offline(B, sh, pc)
+    store = synth.Store(k_rot, pc.v, cu.astype(np.int64))
+    sd = _store_dev(B, sh, store)
+    ids = np.array([2, 0, 1], np.int32)
+    n_q = 24
+    sel = [lens[c] for c in ids]
+    req = synth.Request(ids, synth.POS_REORDERED, n_q, synth.normal_tensor(rng, (n_q, 28, 128), sh.torch_dtype),
+                        synth.normal_tensor(rng, (n_q, 4, 128), sh.torch_dtype), synth.normal_tensor(rng, (n_q, 4, 128), sh.torch_dtype),
+                        (sum(sel) + np.arange(n_q)).astype(np.int32), sum(sel), sel)
+    g = H.run_request_gpu(B, sh, sd, req)
+    # oracle from raw keys: gather raw, rotate once at the reordered (global) ids, plain prefix attention
+    raw_k = np.concatenate([H.bits(pc.k)[cu[c]:cu[c + 1]] for c in ids] + [H.bits(req.k_q)])
+    raw_v = np.concatenate([H.bits(pc.v)[cu[c]:cu[c + 1]] for c in ids] + [H.bits(req.v_q)])
+    all_pos = np.concatenate([np.arange(sum(sel)), req.q_pos])
+    want = oracle.attn_prefix(oracle.rope(H.bits(req.q), req.q_pos, sh.rope_base), oracle.rope(raw_k, all_pos, sh.rope_base),
+                              oracle.widen(raw_v))
+    err = float(np.abs(H.to_f64(g["out"]) - want).max())
+    assert err <= H.BF16_TOL, err
