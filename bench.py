@@ -1,0 +1,294 @@
+#!/usr/bin/env python3
+"""Benchmark of the TurboRAG online-prefill hot path on one MI355X.
+
+A step is one pass of the online path for one request of configuration 2 (Qwen2-7B attention
+shape, 8 retrieved chunks x 512 tokens out of a 256-chunk store, 64 query tokens, reordered
+positions): gather plan -> tr_kv_assemble -> tr_kv_append -> tr_prefill_attn, one layer.
+Steps cycle through 16 requests with different chunk ids and their own cache buffers, so the
+store is read from HBM rather than from a warm cache.  The K timed steps are captured once in a
+HIP graph (the way a serving loop would issue them) and replayed between two synchronisations;
+`eager_us_per_step` is the same loop driven call by call from Python.
+
+The JSON line also carries the roofline of the dominant kernel of the step, the rooflines of the
+other kernels at the sizes where they are bandwidth- or MFMA-bound (configurations 4 and 5), and
+the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+N_VARIANTS = 16
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters read
+# on a copy kernel of known size (see profiles/ and the design doc).  None where not measured.
+MEASURED_TRAFFIC = {}
+
+
+def _events(torch, n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def _time_calls(torch, fn, iters, warmup=3, reps=5):
+    """Average duration (us) of fn's GPU work.  `iters` calls are captured into one HIP graph, so that they run
+    back to back without host launch gaps, and each replay is bracketed by one HIP event pair on the launching
+    stream.  Returns (mean, median, min) over `reps` replays of the per-call average."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(iters):
+            fn()
+    graph.replay()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = _events(torch, 2)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3 / iters)
+    ts.sort()
+    return float(np.mean(ts)), float(ts[len(ts) // 2]), float(ts[0])
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--no-extra", action="store_true", help="skip configurations 4/5 and the CPU baseline")
+    ap.add_argument("--no-graph", action="store_true", help="time the eager loop instead of a HIP graph replay")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_07590_amd import accounting as acct
+    from paper_2410_07590_amd import build as trbuild
+    from paper_2410_07590_amd import synth
+    if not os.path.exists(trbuild.LIB):
+        trbuild.build()
+    from paper_2410_07590_amd import binding as B
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    B.lib()
+    torch.cuda.set_device(0)
+
+    # ------------------------------------------------------------------ configuration 2 workload
+    cfg = synth.CONFIGS[2]
+    sh = cfg.shape
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    store = synth.make_store(cfg)
+    sd = B.Store(gs, store.k.cuda(), store.v.cuda(), store.row_start)
+    base_req = synth.make_requests(cfg, store)[0]
+    rng = synth.rng_for(cfg, 9)
+    variants = []
+    for i in range(N_VARIANTS):
+        ids = base_req.chunk_ids if i == 0 else rng.choice(cfg.store_chunks, size=cfg.chunks_per_request, replace=False).astype(np.int32)
+        offsets, _ = B.tr_plan(sd, ids, base_req.pos_mode, want_pos_ids=False)
+        n_doc = int(offsets[-1])
+        kv_len = n_doc + base_req.n_q
+        variants.append(dict(
+            ids=ids, n_doc=n_doc, kv_len=kv_len,
+            cache_k=torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda"),
+            cache_v=torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda"),
+            out=torch.empty((base_req.n_q, sh.n_q_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda")))
+    q, k_q, v_q = base_req.q.cuda(), base_req.k_q.cuda(), base_req.v_q.cuda()
+    q_pos = torch.from_numpy(base_req.q_pos).cuda()
+    n_q = base_req.n_q
+    ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, n_q, variants[0]["kv_len"]))
+
+    def assemble(v):
+        offsets, _ = B.tr_plan(sd, v["ids"], base_req.pos_mode, want_pos_ids=False)   # a1: plan (host)
+        B.tr_kv_assemble(sd, v["ids"], offsets, base_req.pos_mode, v["cache_k"], v["cache_v"])
+
+    def append(v):
+        B.tr_kv_append(gs, k_q, v_q, q_pos, v["cache_k"], v["cache_v"], v["n_doc"])
+
+    def attn(v):
+        B.tr_prefill_attn(gs, q, v["cache_k"], v["cache_v"], q_pos, v["kv_len"], v["out"], ws)
+
+    def step(i):
+        v = variants[i % N_VARIANTS]
+        assemble(v)
+        append(v)
+        attn(v)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # eager loop (host-driven)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    eager_s = time.perf_counter() - t0
+
+    if args.no_graph:
+        total_s = eager_s
+    else:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(args.steps):
+                step(i)
+        graph.replay()               # untimed: first replay uploads the graph
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        total_s = time.perf_counter() - t0
+    us_per_step = total_s / args.steps * 1e6
+
+    # ------------------------------------------------------------------ per-kernel durations, HIP events
+    it = 64
+    cyc = {"i": 0}
+
+    def cyc_call(fn):
+        def f():
+            cyc["i"] += 1
+            fn(variants[cyc["i"] % N_VARIANTS])
+        return f
+
+    t_asm = _time_calls(torch, cyc_call(assemble), it)
+    t_app = _time_calls(torch, cyc_call(append), it)
+    t_att = _time_calls(torch, cyc_call(attn), it)
+
+    kv_len = variants[0]["kv_len"]
+    eb = sh.elem_bytes
+    asm_bytes = acct.assemble_bytes(variants[0]["n_doc"], sh.n_kv_heads, sh.head_dim, eb)
+    att_flops = acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_prefix(n_q, kv_len))
+    att_bytes = acct.prefill_attn_bytes(n_q, kv_len, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb)
+
+    def hbm_roof(name, workload, nbytes, t_us):
+        a = nbytes / (t_us[0] * 1e-6) / 1e9
+        return {"kernel": name, "workload": workload, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((name, workload)),
+                "avg_us": round(t_us[0], 2), "median_us": round(t_us[1], 2), "algorithmic_bytes": nbytes}
+
+    def mfma_roof(name, workload, flops, t_us, nbytes):
+        a = flops / (t_us[0] * 1e-6) / 1e12
+        return {"kernel": name, "workload": workload, "bound": "mfma", "achieved": round(a, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(a / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get((name, workload)),
+                "avg_us": round(t_us[0], 2), "median_us": round(t_us[1], 2), "algorithmic_flops": flops,
+                "algorithmic_bytes": nbytes, "hbm_gbs": round(nbytes / (t_us[0] * 1e-6) / 1e9, 1)}
+
+    # dominant kernel of the step: query-prefill attention (prefix_attn_kernel + its split-KV combine)
+    roofline = mfma_roof("tr_prefill_attn", cfg.name, att_flops, t_att, att_bytes)
+    roof_extra = [hbm_roof("tr_kv_assemble", cfg.name, asm_bytes, t_asm),
+                  {"kernel": "tr_kv_append", "workload": cfg.name, "avg_us": round(t_app[0], 2), "median_us": round(t_app[1], 2)}]
+
+    result = {
+        "metric": "us/layer query-prefill over assembled KV (plan + assemble + append + prefill attention)",
+        "value": round(us_per_step, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_per_step / 1e3, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 2: %s (28 q heads, 4 kv heads, head_dim 128, 8 of 256 chunks x 512 tokens, 64 query tokens, reordered positions)" % cfg.name,
+                   "timed_as": "eager" if args.no_graph else "hip_graph_replay", "request_variants": N_VARIANTS},
+        "eager_us_per_step": round(eager_s / args.steps * 1e6, 3),
+        "kernel_us": {"assemble": round(t_asm[0], 2), "append": round(t_app[0], 2), "prefill_attn": round(t_att[0], 2)},
+        "roofline": roofline,
+    }
+
+    if not args.no_extra:
+        del sd, store
+        roof_extra += bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof)
+        roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
+        result["cpu_baseline"] = cpu_baseline(synth, cfg)
+    result["roofline_extra"] = roof_extra
+    print(json.dumps(result))
+
+
+def bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof):
+    cfg = synth.CONFIGS[4]
+    sh = cfg.shape
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    store = synth.make_store(cfg)
+    sd = B.Store(gs, store.k.cuda(), store.v.cuda(), store.row_start)
+    req = synth.make_requests(cfg, store)[0]
+    offsets, _ = B.tr_plan(sd, req.chunk_ids, req.pos_mode, want_pos_ids=False)
+    n_doc, kv_len = int(offsets[-1]), int(offsets[-1]) + req.n_q
+    caches = [(torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda"),
+               torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda")) for _ in range(2)]
+    q, k_q, v_q = req.q.cuda(), req.k_q.cuda(), req.v_q.cuda()
+    q_pos = torch.from_numpy(req.q_pos).cuda()
+    out = torch.empty(q.shape, dtype=sh.torch_dtype, device="cuda")
+    ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, req.n_q, kv_len))
+    c = {"i": 0}
+
+    def asm():
+        c["i"] += 1
+        ck, cv = caches[c["i"] % 2]
+        B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
+
+    def att():
+        c["i"] += 1
+        ck, cv = caches[c["i"] % 2]
+        B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
+
+    for ck, cv in caches:
+        B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
+        B.tr_kv_append(gs, k_q, v_q, q_pos, ck, cv, n_doc)
+    t_asm = _time_calls(torch, asm, 30)
+    t_att = _time_calls(torch, att, 30)
+    eb = sh.elem_bytes
+    return [hbm_roof("tr_kv_assemble", cfg.name, acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb), t_asm),
+            mfma_roof("tr_prefill_attn", cfg.name, acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_prefix(req.n_q, kv_len)),
+                      t_att, acct.prefill_attn_bytes(req.n_q, kv_len, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb))]
+
+
+def bench_config5(torch, B, synth, acct, mfma_roof):
+    cfg = synth.CONFIGS[5]
+    sh = cfg.shape
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    pc = synth.make_packed_chunks(cfg)
+    T = pc.q.shape[0]
+    q, k, v = pc.q.cuda(), pc.k.cuda(), pc.v.cuda()
+    cu = torch.from_numpy(pc.cu).cuda()
+    max_len = int(np.diff(pc.cu).max())
+    out = torch.empty(q.shape, dtype=sh.torch_dtype, device="cuda")
+    k_rot = torch.empty(k.shape, dtype=sh.torch_dtype, device="cuda")
+    ws = B.workspace(B.tr_chunk_prefill_attn_workspace_size(gs, T, max_len))
+
+    def run():
+        B.tr_chunk_prefill_attn(gs, q, k, v, cu, pc.cu.size - 1, max_len, out, k_rot, ws)
+
+    t = _time_calls(torch, run, 20)
+    flops = acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_blockdiag(np.diff(pc.cu)))
+    nbytes = acct.chunk_prefill_bytes(T, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.elem_bytes)
+    r = mfma_roof("tr_chunk_prefill_attn", cfg.name, flops, t, nbytes)
+    r["note"] = "whole call: position table + key rotation + block-diagonal attention kernels"
+    return [r]
+
+
+def cpu_baseline(synth, cfg):
+    """The CPU oracle as it stands on one request of configuration 2 (the whole step, not a sample of it)."""
+    import oracle
+    store = synth.make_store(cfg)
+    req = synth.make_requests(cfg, store)[0]
+    bits = synth.as_oracle_array
+    ks, vs = bits(store.k), bits(store.v)
+    qb, kqb, vqb = bits(req.q), bits(req.k_q), bits(req.v_q)
+    best = None
+    for _ in range(2):
+        t0 = time.perf_counter()
+        oracle.online_prefill(ks, vs, store.row_start, req.chunk_ids, req.pos_mode, qb, kqb, vqb, req.q_pos, cfg.shape.rope_base)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return {"value": round(best * 1e6, 1), "unit": "us/layer", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "one full request of configuration 2 (plan, assemble, append, attention; best of 2); "
+                      "fp64, attention loops on all threads, gather and RoPE single-threaded"}
+
+
+if __name__ == "__main__":
+    main()

@@ -4,7 +4,9 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
+#include <algorithm>
 #include <new>
 
 // ---- errors ---------------------------------------------------------------------------------------------------
@@ -308,20 +310,42 @@ namespace {
 struct ReqGeom { int32_t q_row0, n_q; int64_t kv_row0, kv_len; };
 
 constexpr int KEY_TILE = 64;
-constexpr int WG_ROWS_ = 128;
-constexpr int TARGET_ITEMS = 512;   // two 256-thread workgroups per CU on 256 CUs
+constexpr int TARGET_ITEMS = 512;   // workgroup slots to fill: two 4-wave workgroups per CU on 256 CUs
 constexpr int MIN_SPLIT_KEYS = 256;
+constexpr int MAX_SPLIT = 32;       // the combine kernel holds one split per lane of a half-wave
+
+int env_int(const char* name, int dflt)
+{
+    const char* e = getenv(name);
+    return (e && *e) ? atoi(e) : dflt;
+}
+
+// Packed rows per workgroup: 256 (8 waves, deep LDS ring) when one KV head has enough rows to fill such tiles,
+// else 128 (4 waves).  TR_WG_ROWS overrides (tuning aid).
+int pick_wg_rows(const tr_shape* sh, int64_t max_rows_per_kv_head)
+{
+    const int forced = env_int("TR_WG_ROWS", 0);
+    if (forced == 128 || forced == 256) return forced;
+    (void)sh;
+    return max_rows_per_kv_head >= 512 ? 256 : 128;
+}
 
 // Fills the per-request descriptors of one launch (requests [r0, r1)); returns the partial rows it needs.
 int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t r0, size_t r1, TrPrefixArgs* a,
-                    bool* any_split, int* total_tokens)
+                    bool* any_split, int* total_tokens, int* wg_rows_out)
 {
     const int g = sh->n_q_heads / sh->n_kv_heads;
-    const int tpt = WG_ROWS_ / g;
+    int64_t max_rows = 0;
+    for (size_t r = r0; r < r1; ++r) max_rows = std::max<int64_t>(max_rows, (int64_t)reqs[r].n_q * g);
+    const int wg_rows = pick_wg_rows(sh, max_rows);
+    const int tpt = wg_rows / g;
+    const int target = env_int("TR_TARGET_ITEMS", wg_rows == 256 ? TARGET_ITEMS / 2 : TARGET_ITEMS);
+    const int min_split_keys = env_int("TR_MIN_SPLIT_KEYS", MIN_SPLIT_KEYS);
     int64_t base_items = 0;
     for (size_t r = r0; r < r1; ++r) base_items += (int64_t)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads;
     int want_split = 1;
-    if (sh->dtype == TR_BF16 && base_items > 0 && base_items < TARGET_ITEMS) want_split = (int)((TARGET_ITEMS + base_items - 1) / base_items);
+    if (sh->dtype == TR_BF16 && base_items > 0 && base_items < target) want_split = (int)((target + base_items - 1) / base_items);
+    if (want_split > MAX_SPLIT) want_split = MAX_SPLIT;
     int items = 0, n = 0, toks = 0;
     int64_t ws_rows = 0;
     bool any = false;
@@ -329,7 +353,7 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
         const ReqGeom& q = reqs[r];
         if (q.n_q == 0) continue;
         int n_split = want_split;
-        const int64_t max_split = (q.kv_len + MIN_SPLIT_KEYS - 1) / MIN_SPLIT_KEYS;
+        const int64_t max_split = (q.kv_len + min_split_keys - 1) / min_split_keys;
         if (n_split > max_split) n_split = (int)max_split;
         if (n_split < 1) n_split = 1;
         int64_t split_len = (q.kv_len + n_split - 1) / n_split;
@@ -356,9 +380,10 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
             ws_rows += (int64_t)n_split * q.n_q * sh->n_q_heads;
         }
     }
-    if (a) { a->n_seq = n; a->n_items = items; }
+    if (a) { a->n_seq = n; a->n_items = items; a->tok_per_tile = tpt; }
     if (any_split) *any_split = any;
     if (total_tokens) *total_tokens = toks;
+    if (wg_rows_out) *wg_rows_out = wg_rows;
     return ws_rows;
 }
 
@@ -367,7 +392,7 @@ size_t prefix_ws_bytes(const tr_shape* sh, const std::vector<ReqGeom>& reqs)
     size_t need = 0;
     for (size_t r0 = 0; r0 < reqs.size(); r0 += TR_MAX_SEQ) {
         size_t r1 = r0 + TR_MAX_SEQ < reqs.size() ? r0 + TR_MAX_SEQ : reqs.size();
-        int64_t rows = plan_prefix(sh, reqs, r0, r1, nullptr, nullptr, nullptr);
+        int64_t rows = plan_prefix(sh, reqs, r0, r1, nullptr, nullptr, nullptr, nullptr);
         size_t b = tr_align256((size_t)rows * sh->head_dim * 4) + tr_align256((size_t)rows * 8);
         if (b > need) need = b;
     }
@@ -389,7 +414,6 @@ int run_prefix(const tr_shape* sh, const void* q, const void* k, const void* v, 
     a.n_q_heads = sh->n_q_heads;
     a.n_kv_heads = sh->n_kv_heads;
     a.group = sh->n_q_heads / sh->n_kv_heads;
-    a.tok_per_tile = WG_ROWS_ / a.group;
     a.scale = (float)(1.0 / sqrt((double)sh->head_dim));
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)sh->head_dim));
     tr_fill_theta(sh, a.theta);
@@ -397,12 +421,13 @@ int run_prefix(const tr_shape* sh, const void* q, const void* k, const void* v, 
     for (size_t r0 = 0; r0 < reqs.size(); r0 += TR_MAX_SEQ) {
         size_t r1 = r0 + TR_MAX_SEQ < reqs.size() ? r0 + TR_MAX_SEQ : reqs.size();
         bool any_split = false;
-        int toks = 0;
-        int64_t rows = plan_prefix(sh, reqs, r0, r1, &a, &any_split, &toks);
+        int toks = 0, wg_rows = 128;
+        int64_t rows = plan_prefix(sh, reqs, r0, r1, &a, &any_split, &toks, &wg_rows);
         a.ws_o = (float*)ws;
         a.ws_ml = (float*)((char*)ws + tr_align256((size_t)rows * sh->head_dim * 4));
         if (a.n_seq == 0) continue;
-        int rc = tr_launch_prefix_attn(a, sh->dtype, sh->head_dim, any_split, toks * sh->n_q_heads, stream);
+        int rc = sh->dtype == TR_F32 ? tr_launch_prefix_attn_f32(a, sh->head_dim, toks * sh->n_q_heads, stream)
+                                     : tr_launch_prefix_attn(a, sh->head_dim, wg_rows, any_split, toks * sh->n_q_heads, stream);
         if (rc) return rc;
     }
     return TR_OK;
@@ -517,9 +542,11 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
     a.n_q_heads = shape->n_q_heads;
     a.n_kv_heads = shape->n_kv_heads;
     a.group = shape->n_q_heads / shape->n_kv_heads;
-    a.tok_per_tile = WG_ROWS_ / a.group;
+    const int wg_rows = pick_wg_rows(shape, (int64_t)max_chunk_len * a.group);
+    a.tok_per_tile = wg_rows / a.group;
     a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);
     a.scale = (float)(1.0 / sqrt((double)shape->head_dim));
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)shape->head_dim));
-    return tr_launch_blockdiag_attn(a, shape->dtype, shape->head_dim, s);
+    if (shape->dtype == TR_F32) return tr_launch_blockdiag_attn_f32(a, shape->head_dim, s);
+    return tr_launch_blockdiag_attn(a, shape->head_dim, wg_rows, s);
 }

@@ -1,15 +1,25 @@
-// Attention kernels for gfx950.
+// bf16 MFMA attention kernels for gfx950: query prefill over an assembled cache (Sec. 3.4 step 6) and the
+// offline block-diagonal chunk prefill (Sec. 3.4 step 2, independent attention of Sec. 3.2).
 //
-// bf16 path (MFMA): one workgroup = 4 wavefronts = 128 "packed rows"; a packed row is one (query token,
-// query head of the group) pair, so the g query heads that share a KV head sit in the same MFMA tile and
-// every K/V tile fetched from HBM serves all of them.  Each wavefront owns 32 packed rows.
-//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K tile rows (from LDS), B = rotated queries (registers)
-//   O^T = V^T P^T same instruction, A = V^T (transposing LDS reads), B = P^T (registers, straight from S^T)
-// Working on the transposed problem leaves each lane with one query column: the softmax statistics are
-// per-lane scalars, and the S^T accumulator layout is already the B-operand layout of the second product
-// (up to a permutation of the 16 keys inside a k-step, which the V^T reads apply too).
+// Work decomposition.  A "packed row" is one (query token, query head of a GQA group) pair: the g query heads
+// that share a KV head are stacked along the MFMA M dimension, so one K/V tile fetched from HBM serves all of
+// them.  A workgroup of NW wavefronts owns 32*NW packed rows of one KV head; each wavefront owns 32 rows and
+// walks the visible keys in tiles of 64.
 //
-// fp32 path: plain FMA arithmetic, one wavefront per (token, head); for the small fp32 configuration only.
+// Transposed products.  S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16: A = K rows / V^T rows
+// from LDS, B = rotated queries / P^T from registers.  Each lane then owns ONE query column, so the softmax
+// statistics are per-lane scalars, and the S^T accumulator layout already is the B-operand layout of the
+// second product, up to a permutation of the 16 keys inside a k-step that the V^T reads apply as well.
+// V^T operands come from row-major V tiles through the transposing LDS read (ds_read_b64_tr_b16).
+//
+// Data movement.  K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no staging registers) into a
+// ring of NS stages; rows are stored unpadded and XOR-swizzled per 16-byte chunk so that the MFMA operand
+// reads are bank-conflict free.  One s_barrier per tile; s_waitcnt vmcnt counts are managed by hand because
+// the loads are asynchronous with respect to the wave that issued them.
+//
+// Softmax works in the log2 domain with a lazily updated reference maximum: the accumulators are rescaled
+// only when the running maximum grew by more than 2^8, which is exact (softmax is invariant to the reference)
+// and keeps P <= 256.
 #include "tr_internal.h"
 
 namespace {
@@ -19,21 +29,34 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KT = 64;        // keys per tile
+#define LDS_AS __attribute__((address_space(3)))
+#define GLB_AS __attribute__((address_space(1)))
 
-template <int D> struct alignas(16) Smem {
-    static constexpr int KS = D + 8;  // K row stride (elements): 16 B pad -> conflict-free 16 B row reads
-    static constexpr int VS = D + 32; // V row stride: 64 B pad -> 4 consecutive rows x 64 B hit distinct banks
-    __bf16 k[KT][KS];
-    __bf16 v[KT][VS];
+constexpr int KT = 64;               // keys per tile
+constexpr float RESCALE_SLACK = 8.f; // log2 units the running maximum may exceed the reference before a rescale
+
+template <int D> struct Geo {
+    static constexpr int CPR = D / 8;            // 16-byte chunks per row of one head
+    static constexpr int RPI = 64 / CPR;         // rows moved by one wave-wide 1 KB load
+    static constexpr int NI = KT / RPI;          // such loads per K (or V) tile
+    static constexpr int TILE_BYTES = KT * D * 2;
+    static constexpr int STAGE_BYTES = 2 * TILE_BYTES; // K tile then V tile
+    static constexpr int GPR = CPR / 4;          // 64-byte groups per row
+    // K: chunk c of row r sits at chunk c ^ kswz(r): 16 consecutive rows of one logical chunk cover all banks
+    __device__ static __forceinline__ int kswz(int r) { return (r / (16 / CPR)) & (CPR - 1); }
+    // V: 64-byte group q of row r sits at group q ^ vswz(r): 4 consecutive rows of one group cover all banks
+    __device__ static __forceinline__ int vswz(int r) { return (r / (4 / GPR)) & (GPR - 1); }
 };
+
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+template <int N> __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt(vmcnt_imm(N)); }
 
 struct RowCtx {
     bool valid;
-    int q_tok;   // row of q / out
-    int head;    // query head
+    int orow;    // q_tok * n_q_heads + head: row of q / out in units of head vectors
     int key_lo;  // first visible cache row
     int key_hi;  // last visible cache row
     double pos;  // RoPE position id of the query token
@@ -51,184 +74,267 @@ __device__ __forceinline__ int xcd_remap(int bid, int n)
     return x * q + (x < r ? x : r) + idx;
 }
 
-__device__ __forceinline__ int wave_max32(int v)
+__device__ __forceinline__ int wave_max_i(int v)
 {
 #pragma unroll
-    for (int o = 16; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o));
-    v = max(v, __shfl_xor(v, 32));
+    for (int o = 32; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o));
     return __builtin_amdgcn_readfirstlane(v);
 }
-__device__ __forceinline__ int wave_min32(int v)
+__device__ __forceinline__ int wave_min_i(int v)
 {
 #pragma unroll
-    for (int o = 16; o >= 1; o >>= 1) v = min(v, __shfl_xor(v, o));
-    v = min(v, __shfl_xor(v, 32));
+    for (int o = 32; o >= 1; o >>= 1) v = min(v, __shfl_xor(v, o));
     return __builtin_amdgcn_readfirstlane(v);
 }
 
-// Rotated query fragments: lane (c = lane & 31, h = lane >> 5) holds Q'[row c][16 ks + 8 h .. +7].
+// Rotated query fragments (Eq. 3 at the token's position id): lane (c = lane & 31, h = lane >> 5) holds
+// Q'[row c][16 ks + 8 h .. +7].  Angles are reduced in fp64 to [-1/2, 1/2] revolutions, then v_sin/v_cos.
 template <int D>
-__device__ __forceinline__ void load_q_frags(const __bf16* __restrict__ q, int n_q_heads, const RowCtx& rc,
-                                             const double* theta_rev, int h, bf16x8 (&qf)[D / 16])
+__device__ __forceinline__ void load_q_frags(const __bf16* __restrict__ q, const RowCtx& rc, const double* theta_rev,
+                                             int h, bf16x8 (&qf)[D / 16])
 {
+    // all loads first (one round trip), rows that do not exist read row 0 and are zeroed
+    const __bf16* qrow = q + (int64_t)(rc.valid ? rc.orow : 0) * D + 8 * h;
+    uint4 raw[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) raw[ks] = *(const uint4*)(qrow + 16 * ks);
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
         bf16x8 f;
+        const uint32_t w[4] = {raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = (__bf16)0.0f;
-        if (rc.valid) {
-            const int d0 = 16 * ks + 8 * h;
-            const uint4 raw = *(const uint4*)(q + ((int64_t)rc.q_tok * n_q_heads + rc.head) * D + d0);
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const double t0 = theta_rev[8 * ks + p], t1 = theta_rev[8 * ks + 4 + p];
-                double rev = rc.pos * (h ? t1 : t0);
-                rev -= rint(rev);
-                const float x = (float)rev;
-                const float sn = __builtin_amdgcn_sinf(x), cn = __builtin_amdgcn_cosf(x);
-                const float xa = bf_lo(w[p]), xb = bf_hi(w[p]);
-                f[2 * p] = (__bf16)(xa * cn - xb * sn);
-                f[2 * p + 1] = (__bf16)(xb * cn + xa * sn);
-            }
+        for (int p = 0; p < 4; ++p) {
+            const double t0 = theta_rev[8 * ks + p], t1 = theta_rev[8 * ks + 4 + p];
+            double rev = rc.pos * (h ? t1 : t0);
+            rev -= rint(rev);
+            const float x = (float)rev;
+            const float sn = __builtin_amdgcn_sinf(x), cn = __builtin_amdgcn_cosf(x);
+            const float xa = rc.valid ? bf_lo(w[p]) : 0.0f, xb = rc.valid ? bf_hi(w[p]) : 0.0f;
+            f[2 * p] = (__bf16)(xa * cn - xb * sn);
+            f[2 * p + 1] = (__bf16)(xb * cn + xa * sn);
         }
         qf[ks] = f;
     }
 }
 
-// The tile loop shared by the prefix and the block-diagonal kernels.
-// kt_begin..kt_end: cache rows this workgroup walks (workgroup-uniform); key_clamp: last row that may be
-// loaded; a tile [kt, kt+KT) needs per-element masking iff kt+KT-1 > mask_hi_min or kt < mask_lo_max.
-template <int D>
-__device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const __bf16* __restrict__ v, int n_kv_heads,
-                                           int kvh, const RowCtx& rc, const bf16x8 (&qf)[D / 16], int kt_begin,
-                                           int kt_end, int key_clamp, int mask_hi_min, int mask_lo_max,
-                                           float sl2e, Smem<D>& sm, f32x16 (&o)[D / 32], float& m_run, float& l_run)
+// Per-wave state of the tile loop.
+template <int D> struct Acc {
+    f32x16 o[D / 32]; // O^T: element e of block db is channel 32 db + 8 (e >> 2) + 4 h + (e & 3) of query column c
+    float mref;       // reference maximum, log2 domain (score * log2(e)/sqrt(d))
+    float l;          // this half-wave's share of the softmax denominator
+};
+
+// Issue this wave's share of the direct global->LDS loads of tile [kt, kt+64) into one stage.
+template <int D, int NW>
+__device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const __bf16* __restrict__ v, int64_t row_elems,
+                                           int head_off, int kt, int key_clamp, LDS_AS char* stage, int wave, int lane)
 {
-    constexpr int UPR = D / 8;              // 16-byte units per K row of one head
-    constexpr int LOADS = KT * UPR / 256;   // units per thread per tile
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int c = lane & 31, h = lane >> 5;
-    const int i16 = lane & 15, colhalf = (lane >> 4) & 1;
+    using G = Geo<D>;
+    const int r_in = lane / G::CPR, pc = lane % G::CPR;
+#pragma unroll
+    for (int ii = 0; ii < G::NI / NW; ++ii) {
+        const int i = wave + NW * ii;
+        const int row = i * G::RPI + r_in;
+        int key = kt + row;
+        key = key > key_clamp ? key_clamp : key;
+        const int ck = pc ^ G::kswz(row);
+        const int cv = 4 * ((pc >> 2) ^ G::vswz(row)) + (pc & 3);
+        const int64_t base = (int64_t)key * row_elems + head_off;
+        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(k + base + ck * 8), (LDS_AS void*)(stage + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(v + base + cv * 8),
+                                         (LDS_AS void*)(stage + G::TILE_BYTES + i * 1024), 16, 0, 0);
+    }
+}
 
-    const int wave_hi_max = wave_max32(rc.valid ? rc.key_hi : INT32_MIN);
-    const int wave_lo_min = wave_min32(rc.valid ? rc.key_lo : INT32_MAX);
-
-    u32x4 kreg[LOADS], vreg[LOADS];
-    auto issue_loads = [&](int kt) {
+// One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.
+template <int D>
+__device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf16x8 (&qf)[D / 16], const RowCtx& rc, int kt,
+                                             bool need_mask, float sl2e, const int (&koff)[D / 16], const int (&voff)[D / 32], int h,
+                                             Acc<D>& acc)
+{
+    using G = Geo<D>;
+    f32x16 s[2];
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx / UPR, u = idx % UPR;
-            int key = kt + row;
-            key = key > key_clamp ? key_clamp : key;
-            const int64_t off = ((int64_t)key * n_kv_heads + kvh) * D + u * 8;
-            kreg[i] = *(const u32x4*)(k + off);
-            vreg[i] = *(const u32x4*)(v + off);
-        }
-    };
-    auto store_lds = [&]() {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx / UPR, u = idx % UPR;
-            *(u32x4*)&sm.k[row][u * 8] = kreg[i];
-            *(u32x4*)&sm.v[row][u * 8] = vreg[i];
-        }
-    };
-
-    if (kt_begin < kt_end) issue_loads(kt_begin);
-    for (int kt = kt_begin; kt < kt_end; kt += KT) {
-        __syncthreads(); // every wave is done reading the previous tile
-        store_lds();
-        __syncthreads();
-        if (kt + KT < kt_end) issue_loads(kt + KT); // in flight while this tile is computed
-
-        const bool active = (kt <= wave_hi_max) && (kt + KT - 1 >= wave_lo_min); // wave-uniform
-        if (!active) continue;
-
-        // ---- S^T = K Q^T : two 32-key blocks
-        f32x16 s[2];
+        for (int e = 0; e < 16; ++e) s[kb][e] = 0.0f;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[kb][e] = 0.0f;
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
-            const bf16x8 a0 = *(const bf16x8*)&sm.k[c][16 * ks + 8 * h];
-            const bf16x8 a1 = *(const bf16x8*)&sm.k[32 + c][16 * ks + 8 * h];
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s[1], 0, 0, 0);
-        }
-        // accumulator element e of block kb is key kt + 32 kb + 8 (e >> 2) + 4 h + (e & 3), query column c
-        const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
-        if (need_mask) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = kt + 32 * kb + 8 * (e >> 2) + 4 * h + (e & 3);
-                    if (key < rc.key_lo || key > rc.key_hi) s[kb][e] = -INFINITY;
-                }
-        }
-        // ---- online softmax; the two half-waves hold the two key halves of the same query column
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * sl2e);
-        const float mb = m_use * sl2e;
-        float lsum = 0.0f;
+    for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 a0 = *(LDS_AS const bf16x8*)(stage + koff[ks]);
+        const bf16x8 a1 = *(LDS_AS const bf16x8*)(stage + koff[ks] + 32 * D * 2);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s[1], 0, 0, 0);
+    }
+    // accumulator element e of block kb is key kt + 32 kb + 8 (e >> 2) + 4 h + (e & 3), query column c
+    if (need_mask) { // workgroup-uniform: only tiles that straddle a mask edge
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][e], sl2e, -mb));
-                s[kb][e] = p;
-                lsum += p;
+                const int key = kt + 32 * kb + 8 * (e >> 2) + 4 * h + (e & 3);
+                if (key < rc.key_lo || key > rc.key_hi) s[kb][e] = -INFINITY;
             }
-        l_run = l_run * alpha + lsum;
-        m_run = m_new;
-        if (__any(alpha != 1.0f)) {
+    }
+    float mx = -INFINITY;
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32)) * sl2e; // both half-waves hold keys of the same query column
+    // lazy reference update (exact: any reference gives the same softmax)
+    const bool grow = mx > acc.mref + RESCALE_SLACK;
+    if (__any(grow)) {
+        // lanes that do not grow keep their reference (alpha = 1; note -inf - -inf would be NaN);
+        // mref = -inf on a row's first visible tile gives alpha = 0, and the accumulators are still 0
+        const float alpha = grow ? __builtin_amdgcn_exp2f(acc.mref - mx) : 1.0f;
+        acc.mref = grow ? mx : acc.mref;
+        acc.l *= alpha;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc.o[db][e] *= alpha;
+    }
+    const float mb = (acc.mref == -INFINITY) ? 0.0f : acc.mref; // nothing visible yet: every p below is exp2(-inf) = 0
+    float lsum = 0.0f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][e], sl2e, -mb));
+            s[kb][e] = p;
+            lsum += p;
         }
-        // ---- O^T += V^T P^T
+    acc.l += lsum;
+    // O^T += V^T P^T.  k-slot j of k-step (kb, t) is key 32 kb + 16 t + 8 (j >> 2) + 4 h + (j & 3).
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                bf16x8 bp;
+        for (int t = 0; t < 2; ++t) {
+            bf16x8 bp;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) bp[e] = (__bf16)s[kb][8 * t + e];
-                // k-slot j of this k-step is key 32 kb + 16 t + 8 (j >> 2) + 4 h + (j & 3)
-                const int krow = 32 * kb + 16 * t + 4 * h + (i16 >> 2);
+            for (int e = 0; e < 8; ++e) bp[e] = (__bf16)s[kb][8 * t + e];
+            const int rbase = G::TILE_BYTES + (32 * kb + 16 * t) * D * 2;
 #pragma unroll
-                for (int db = 0; db < D / 32; ++db) {
-                    const __bf16* p0 = &sm.v[krow][32 * db + 16 * colhalf + 4 * (i16 & 3)];
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0 + 8 * Smem<D>::VS));
-                    const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), bp, o[db], 0, 0, 0);
+            for (int db = 0; db < D / 32; ++db) {
+                LDS_AS const char* p0 = stage + rbase + voff[db];
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 8 * D * 2));
+                const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), bp, acc.o[db], 0, 0, 0);
+            }
+        }
+}
+
+// The tile loop shared by both kernels.  kt_begin..kt_end: cache rows this workgroup walks (workgroup-uniform);
+// key_clamp: last row that may be loaded; tile [kt, kt+64) needs per-element masking iff
+// kt+63 > mask_hi_min or kt < mask_lo_max.
+template <int D, int NW, int NS>
+__device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const __bf16* __restrict__ v, int n_kv_heads,
+                                           int kvh, const RowCtx& rc, const bf16x8 (&qf)[D / 16], int kt_begin,
+                                           int kt_end, int key_clamp, int mask_hi_min, int mask_lo_max, float sl2e,
+                                           LDS_AS char* smem, Acc<D>& acc)
+{
+    using G = Geo<D>;
+    constexpr int IPW = 2 * G::NI / NW; // loads each wave issues per tile
+    static_assert(G::NI % NW == 0, "tile loads must divide evenly over the waves");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int i16 = lane & 15, colhalf = (lane >> 4) & 1;
+
+    const int wave_hi_max = wave_max_i(rc.valid ? rc.key_hi : INT32_MIN);
+    const int wave_lo_min = wave_min_i(rc.valid ? rc.key_lo : INT32_MAX);
+
+    // LDS byte offsets of this lane's operands inside a stage
+    int koff[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) koff[ks] = c * D * 2 + (((2 * ks + h) ^ G::kswz(c)) * 16);
+    int voff[D / 32];
+    {
+        const int r = 4 * h + (i16 >> 2); // row inside an 8-row k-slot block; rows 8 apart share the swizzle
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+            voff[db] = r * D * 2 + (4 * (db ^ G::vswz(r)) + 2 * colhalf + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
+    }
+
+    const int64_t row_elems = (int64_t)n_kv_heads * D;
+    const int head_off = kvh * D;
+    const int n_tiles = kt_end > kt_begin ? (kt_end - kt_begin + KT - 1) / KT : 0;
+
+    // prologue: tiles 0 .. NS-2 in flight
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < n_tiles) issue_tile<D, NW>(k, v, row_elems, head_off, kt_begin + p * KT, key_clamp, smem + p * G::STAGE_BYTES, wave, lane);
+
+    for (int t = 0; t < n_tiles; ++t) {
+        const int kt = kt_begin + t * KT;
+        // tile t has landed once at most the loads of the tiles issued after it are outstanding
+        const int later = min(NS - 2, n_tiles - 1 - t);
+        if (NS >= 4 && later >= 2) wait_vm<2 * IPW>();
+        else if (NS >= 3 && later >= 1) wait_vm<IPW>();
+        else wait_vm<0>();
+        __builtin_amdgcn_s_barrier(); // every wave's share of tile t is in LDS; everyone is done with tile t-1
+        if (t + NS - 1 < n_tiles)
+            issue_tile<D, NW>(k, v, row_elems, head_off, kt + (NS - 1) * KT, key_clamp,
+                              smem + ((t + NS - 1) % NS) * G::STAGE_BYTES, wave, lane);
+        const bool active = (kt <= wave_hi_max) && (kt + KT - 1 >= wave_lo_min); // wave-uniform
+        if (active) {
+            LDS_AS const char* stage = smem + (t % NS) * G::STAGE_BYTES;
+            const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
+            compute_tile<D>(stage, qf, rc, kt, need_mask, sl2e, koff, voff, h, acc);
+        }
+    }
+}
+
+// Write the wave's 32 x D accumulator as rows: stage O^T through LDS (64 channels at a time) so that every
+// global store instruction writes whole contiguous row segments.
+//   PARTIAL = false: out[orow][:] = bf16(O / l)          PARTIAL = true: ws_o[prow][:] = O (fp32, unnormalised)
+template <int D, bool PARTIAL>
+__device__ __forceinline__ void store_rows(const Acc<D>& acc, float l_tot, bool valid, int64_t dst_row, void* dst,
+                                           LDS_AS char* wave_buf, int lane)
+{
+    constexpr int STRIDE = 64 * 4 + 16; // bytes per staged row: 64 floats + pad
+    const int c = lane & 31, h = lane >> 5;
+    const float inv = PARTIAL ? 1.0f : 1.0f / l_tot;
+    const int r_in = lane >> 4, c4 = lane & 15;
+#pragma unroll
+    for (int half = 0; half < D / 64; ++half) {
+#pragma unroll
+        for (int dbl = 0; dbl < 2; ++dbl)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int db = 2 * half + dbl;
+                f32x4 x;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = acc.o[db][4 * q4 + e] * inv;
+                *(LDS_AS f32x4*)(wave_buf + c * STRIDE + (32 * dbl + 8 * q4 + 4 * h) * 4) = x;
+            }
+        // 4 rows per instruction: lane -> (row 4 rr + lane / 16, channels 4 (lane % 16) .. +3 of this half)
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const int row = 4 * rr + r_in;
+            const f32x4 x = *(LDS_AS const f32x4*)(wave_buf + row * STRIDE + c4 * 16);
+            const int64_t drow = __shfl(dst_row, row);       // row's owner lane is lane `row` (c == row, h == 0)
+            const int ok = __shfl((int)valid, row);
+            if (ok) {
+                if (PARTIAL) {
+                    *(f32x4*)((float*)dst + drow * D + 64 * half + 4 * c4) = x;
+                } else {
+                    bf16x4 y;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] = (__bf16)x[e];
+                    *(bf16x4*)((__bf16*)dst + drow * D + 64 * half + 4 * c4) = y;
                 }
             }
+        }
     }
 }
 
 // ---- step 6: query prefill over the assembled cache -------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256, 2) void prefix_attn_kernel(const TrPrefixArgs a)
+template <int D, int NW, int NS>
+__global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixArgs a)
 {
-    __shared__ Smem<D> sm;
+    extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+    LDS_AS char* smem = (LDS_AS char*)smem_raw;
     const int item = xcd_remap(blockIdx.x, a.n_items);
     int lo = 0, hi = a.n_seq - 1;
     while (lo < hi) {
@@ -250,11 +356,10 @@ __global__ __launch_bounds__(256, 2) void prefix_attn_kernel(const TrPrefixArgs 
     const int tok_local = tile * tpt + rl / g;
     RowCtx rc;
     rc.valid = (rl < tpt * g) && (tok_local < sd.n_q);
-    rc.q_tok = sd.q_row0 + tok_local;
-    rc.head = kvh * g + rl % g;
+    rc.orow = (sd.q_row0 + tok_local) * a.n_q_heads + kvh * g + rl % g;
     rc.key_lo = sd.kv_row0;
     rc.key_hi = sd.kv_row0 + n_doc + tok_local;
-    rc.pos = rc.valid ? (double)a.q_pos[rc.q_tok] : 0.0;
+    rc.pos = rc.valid ? (double)a.q_pos[sd.q_row0 + tok_local] : 0.0;
 
     const int first_tok = tile * tpt;
     const int last_tok = min(first_tok + tpt, sd.n_q) - 1;
@@ -264,55 +369,42 @@ __global__ __launch_bounds__(256, 2) void prefix_attn_kernel(const TrPrefixArgs 
     const int kt_end = min(se, sd.kv_row0 + n_doc + last_tok + 1);
 
     bf16x8 qf[D / 16];
-    load_q_frags<D>((const __bf16*)a.q, a.n_q_heads, rc, a.theta_rev, h, qf);
+    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, qf);
 
-    f32x16 o[D / 32];
+    Acc<D> acc;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+        for (int e = 0; e < 16; ++e) acc.o[db][e] = 0.0f;
+    acc.mref = -INFINITY;
+    acc.l = 0.0f;
 
-    attn_tiles<D>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, kt_begin, kt_end,
-                  sd.kv_row0 + sd.kv_len - 1, sd.kv_row0 + n_doc + first_tok, sd.kv_row0, a.scale_log2e, sm, o,
-                  m_run, l_run);
+    attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, kt_begin, kt_end,
+                          sd.kv_row0 + sd.kv_len - 1, sd.kv_row0 + n_doc + first_tok, sd.kv_row0, a.scale_log2e, smem, acc);
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (!rc.valid) return;
-    // accumulator element e of block db is channel 32 db + 8 (e >> 2) + 4 h + (e & 3)
+    const float l_tot = acc.l + __shfl_xor(acc.l, 32);
+    __builtin_amdgcn_s_barrier(); // all waves are done with the K/V stages; reuse them as store staging
+    LDS_AS char* wave_buf = smem + wave * (32 * (64 * 4 + 16));
     if (sd.n_split == 1) {
-        const float inv = 1.0f / l_tot;
-        __bf16* op = (__bf16*)a.out + ((int64_t)rc.q_tok * a.n_q_heads + rc.head) * D;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                bf16x4 r;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) r[e] = (__bf16)(o[db][4 * q4 + e] * inv);
-                *(bf16x4*)(op + 32 * db + 8 * q4 + 4 * h) = r;
-            }
+        store_rows<D, false>(acc, l_tot, rc.valid, (int64_t)rc.orow, a.out, wave_buf, lane);
     } else {
         const int rows_s = sd.n_q * g;
         const int64_t prow = (int64_t)sd.ws_row0 + (int64_t)(split * a.n_kv_heads + kvh) * rows_s + tok_local * g + rl % g;
-        float* wp = a.ws_o + prow * D;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                *(float4*)(wp + 32 * db + 8 * q4 + 4 * h) =
-                    make_float4(o[db][4 * q4], o[db][4 * q4 + 1], o[db][4 * q4 + 2], o[db][4 * q4 + 3]);
-        if (h == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(m_run, l_tot);
+        store_rows<D, true>(acc, l_tot, rc.valid, prow, a.ws_o, wave_buf, lane);
+        if (rc.valid && h == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(acc.mref, l_tot);
     }
 }
 
-// Merge the split-KV partial results: out = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^((m_s - max m) * sl2e)
+// Merge the split-KV partial results: out = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).
+// 32 lanes per output row (4 channels each); lane i of the row also owns split i's statistics.
 template <int D>
 __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int total_rows)
 {
-    constexpr int TPR = D / 4; // threads per output row, 4 channels each
-    const int64_t R = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
-    const int d4 = threadIdx.x % TPR;
+    static_assert(D == 128 || D == 64, "");
+    constexpr int LPR = 32;                     // lanes per row
+    constexpr int CPLN = D / LPR;               // channels per lane: 4 or 2
+    const int lane_r = threadIdx.x & 31;
+    const int64_t R = (int64_t)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
     if (R >= total_rows) return;
     const int tq = a.seq[0].q_row0 + (int)(R / a.n_q_heads);
     const int hq = (int)(R % a.n_q_heads);
@@ -325,34 +417,60 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
     if (sd.n_split == 1) return;
     const int g = a.group;
     const int kvh = hq / g;
-    const int rows_s = sd.n_q * g;
-    const int r = (tq - sd.q_row0) * g + hq % g;
-    float M = -INFINITY;
-    for (int sp = 0; sp < sd.n_split; ++sp) {
-        const int64_t prow = (int64_t)sd.ws_row0 + (int64_t)(sp * a.n_kv_heads + kvh) * rows_s + r;
-        M = fmaxf(M, a.ws_ml[prow * 2]);
+    const int64_t rows_s = (int64_t)sd.n_q * g;
+    const int64_t prow0 = (int64_t)sd.ws_row0 + kvh * rows_s + (tq - sd.q_row0) * g + hq % g;
+    const int64_t pstride = (int64_t)a.n_kv_heads * rows_s; // partial rows between consecutive splits
+    // statistics: lane i < n_split (n_split <= 32) loads split i
+    float m_i = -INFINITY, l_i = 0.0f;
+    if (lane_r < sd.n_split) {
+        const float2 ml = *(const float2*)(a.ws_ml + (prow0 + lane_r * pstride) * 2);
+        m_i = ml.x;
+        l_i = ml.y;
     }
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float L = 0.0f;
+    float M = m_i;
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+    const float w_i = (m_i == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_i - M);
+    float L = w_i * l_i;
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) L += __shfl_xor(L, o);
+    float acc[CPLN];
+#pragma unroll
+    for (int e = 0; e < CPLN; ++e) acc[e] = 0.0f;
+    const float* base = a.ws_o + prow0 * D + CPLN * lane_r;
+    const int row_lane0 = threadIdx.x & 32; // first lane of this row's half-wave
     for (int sp = 0; sp < sd.n_split; ++sp) {
-        const int64_t prow = (int64_t)sd.ws_row0 + (int64_t)(sp * a.n_kv_heads + kvh) * rows_s + r;
-        const float2 ml = *(const float2*)(a.ws_ml + prow * 2);
-        const float w = __builtin_amdgcn_exp2f((ml.x - M) * a.scale_log2e);
-        const float4 x = *(const float4*)(a.ws_o + prow * D + 4 * d4);
-        acc.x += w * x.x; acc.y += w * x.y; acc.z += w * x.z; acc.w += w * x.w;
-        L += w * ml.y;
+        const float w = __shfl(w_i, row_lane0 + sp);
+        const float* p = base + sp * pstride * D;
+        if (CPLN == 4) {
+            const f32x4 x = *(const f32x4*)p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += w * x[e];
+        } else {
+            const float2 x = *(const float2*)p;
+            acc[0] += w * x.x;
+            acc[1] += w * x.y;
+        }
     }
     const float inv = 1.0f / L;
-    bf16x4 rr;
-    rr[0] = (__bf16)(acc.x * inv); rr[1] = (__bf16)(acc.y * inv); rr[2] = (__bf16)(acc.z * inv); rr[3] = (__bf16)(acc.w * inv);
-    *(bf16x4*)((__bf16*)a.out + ((int64_t)tq * a.n_q_heads + hq) * D + 4 * d4) = rr;
+    __bf16* op = (__bf16*)a.out + ((int64_t)tq * a.n_q_heads + hq) * D + CPLN * lane_r;
+    if (CPLN == 4) {
+        bf16x4 y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = (__bf16)(acc[e] * inv);
+        *(bf16x4*)op = y;
+    } else {
+        op[0] = (__bf16)(acc[0] * inv);
+        op[1] = (__bf16)(acc[1] * inv);
+    }
 }
 
 // ---- step 2 (offline): block-diagonal causal attention over packed chunks --------------------------------------
-template <int D>
-__global__ __launch_bounds__(256, 2) void blockdiag_attn_kernel(const TrBlockDiagArgs a)
+template <int D, int NW, int NS>
+__global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBlockDiagArgs a)
 {
-    __shared__ Smem<D> sm;
+    extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+    LDS_AS char* smem = (LDS_AS char*)smem_raw;
     const int n_items = a.n_tiles * a.n_kv_heads;
     const int item = xcd_remap(blockIdx.x, n_items);
     const int tile = item % a.n_tiles;
@@ -366,8 +484,7 @@ __global__ __launch_bounds__(256, 2) void blockdiag_attn_kernel(const TrBlockDia
     const int t = tile * tpt + rl / g;
     RowCtx rc;
     rc.valid = (rl < tpt * g) && (t < T);
-    rc.q_tok = t;
-    rc.head = kvh * g + rl % g;
+    rc.orow = t * a.n_q_heads + kvh * g + rl % g;
     rc.key_lo = rc.valid ? a.tok_start[t] : 0;
     rc.key_hi = t;
     rc.pos = (double)(t - rc.key_lo);
@@ -378,172 +495,74 @@ __global__ __launch_bounds__(256, 2) void blockdiag_attn_kernel(const TrBlockDia
     const int lo_last = a.tok_start[t_last];
 
     bf16x8 qf[D / 16];
-    load_q_frags<D>((const __bf16*)a.q, a.n_q_heads, rc, a.theta_rev, h, qf);
+    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, qf);
 
-    f32x16 o[D / 32];
+    Acc<D> acc;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+        for (int e = 0; e < 16; ++e) acc.o[db][e] = 0.0f;
+    acc.mref = -INFINITY;
+    acc.l = 0.0f;
 
-    attn_tiles<D>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, lo_first, t_last + 1, T - 1,
-                  t_first, lo_last, a.scale_log2e, sm, o, m_run, l_run);
+    attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, lo_first, t_last + 1, T - 1,
+                          t_first, lo_last, a.scale_log2e, smem, acc);
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (!rc.valid) return;
-    const float inv = 1.0f / l_tot;
-    __bf16* op = (__bf16*)a.out + ((int64_t)rc.q_tok * a.n_q_heads + rc.head) * D;
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            bf16x4 r;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) r[e] = (__bf16)(o[db][4 * q4 + e] * inv);
-            *(bf16x4*)(op + 32 * db + 8 * q4 + 4 * h) = r;
-        }
+    const float l_tot = acc.l + __shfl_xor(acc.l, 32);
+    __builtin_amdgcn_s_barrier();
+    LDS_AS char* wave_buf = smem + wave * (32 * (64 * 4 + 16));
+    store_rows<D, false>(acc, l_tot, rc.valid, (int64_t)rc.orow, a.out, wave_buf, lane);
 }
 
-// ---- fp32 path ----------------------------------------------------------------------------------------------
-// One wavefront per (query token, query head).  Keys are walked in blocks of 256: scores with lane <-> key,
-// then the weighted sum with lane <-> channel.  Queries are rotated in fp64.
-struct F32Row {
-    const float* q;   // raw query vector
-    float* out;
-    int key_lo, key_hi, kvh;
-    double pos;
-};
-
-template <int D>
-__device__ __forceinline__ void attn_f32_row(const F32Row& r, const float* __restrict__ k, const float* __restrict__ v,
-                                             int n_kv_heads, const double* theta, float scale)
+template <int D, int NW, int NS> constexpr int smem_bytes()
 {
-    __shared__ float qs[D];
-    __shared__ float ps[256];
-    const int lane = threadIdx.x;
-    for (int m = lane; m < D / 2; m += 64) {
-        double sn, cn;
-        sincos(r.pos * theta[m], &sn, &cn);
-        const double xa = (double)r.q[2 * m], xb = (double)r.q[2 * m + 1];
-        qs[2 * m] = (float)(xa * cn - xb * sn);
-        qs[2 * m + 1] = (float)(xb * cn + xa * sn);
-    }
-    __syncthreads();
-    constexpr int CPL = D / 64; // channels per lane
-    float o[CPL];
-#pragma unroll
-    for (int e = 0; e < CPL; ++e) o[e] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
-    for (int kb = r.key_lo; kb <= r.key_hi; kb += 256) {
-        float s[4];
-        float bmax = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int j = kb + 64 * t + lane;
-            s[t] = -INFINITY;
-            if (j <= r.key_hi) {
-                const float4* kp = (const float4*)(k + ((int64_t)j * n_kv_heads + r.kvh) * D);
-                float acc = 0.0f;
-#pragma unroll 4
-                for (int e = 0; e < D / 4; ++e) {
-                    const float4 x = kp[e];
-                    acc = fmaf(qs[4 * e], x.x, acc);
-                    acc = fmaf(qs[4 * e + 1], x.y, acc);
-                    acc = fmaf(qs[4 * e + 2], x.z, acc);
-                    acc = fmaf(qs[4 * e + 3], x.w, acc);
-                }
-                s[t] = acc * scale;
-            }
-            bmax = fmaxf(bmax, s[t]);
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) bmax = fmaxf(bmax, __shfl_xor(bmax, off));
-        const float m_new = fmaxf(m_run, bmax); // the block holds at least one visible key, so it is finite
-        const float alpha = expf(m_run - m_new);
-        float lsum = 0.0f;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const float p = expf(s[t] - m_new);
-            ps[64 * t + lane] = p;
-            lsum += p;
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) lsum += __shfl_xor(lsum, off);
-        l_run = l_run * alpha + lsum;
-        m_run = m_new;
-#pragma unroll
-        for (int e = 0; e < CPL; ++e) o[e] *= alpha;
-        __syncthreads();
-        const int nk = min(256, r.key_hi - kb + 1);
-        for (int jj = 0; jj < nk; ++jj) {
-            const float p = ps[jj];
-            const float* vp = v + ((int64_t)(kb + jj) * n_kv_heads + r.kvh) * D;
-#pragma unroll
-            for (int e = 0; e < CPL; ++e) o[e] = fmaf(p, vp[lane + 64 * e], o[e]);
-        }
-        __syncthreads();
-    }
-    const float inv = 1.0f / l_run;
-#pragma unroll
-    for (int e = 0; e < CPL; ++e) r.out[lane + 64 * e] = o[e] * inv;
+    constexpr int stages = NS * Geo<D>::STAGE_BYTES;
+    constexpr int staging = NW * 32 * (64 * 4 + 16);
+    return stages > staging ? stages : staging;
 }
 
-template <int D>
-__global__ __launch_bounds__(64) void prefix_attn_f32_kernel(const TrPrefixArgs a)
+template <int D, int NW, int NS>
+int launch_prefix(const TrPrefixArgs& a, hipStream_t s)
 {
-    // block = (packed token of this launch, query head)
-    const int tq = a.seq[0].q_row0 + blockIdx.x / a.n_q_heads;
-    const int hq = blockIdx.x % a.n_q_heads;
-    int lo = 0, hi = a.n_seq - 1;
-    while (lo < hi) {
-        int mid = (lo + hi + 1) >> 1;
-        if (a.seq[mid].q_row0 <= tq) lo = mid; else hi = mid - 1;
+    auto kern = prefix_attn_kernel<D, NW, NS>;
+    constexpr int lds = smem_bytes<D, NW, NS>();
+    static bool configured = false;
+    if (!configured) {
+        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        configured = true;
     }
-    const TrSeqDesc sd = a.seq[lo];
-    const int i = tq - sd.q_row0;
-    F32Row r;
-    r.q = (const float*)a.q + ((int64_t)tq * a.n_q_heads + hq) * D;
-    r.out = (float*)a.out + ((int64_t)tq * a.n_q_heads + hq) * D;
-    r.key_lo = sd.kv_row0;
-    r.key_hi = sd.kv_row0 + (sd.kv_len - sd.n_q) + i;
-    r.kvh = hq / a.group;
-    r.pos = (double)a.q_pos[tq];
-    attn_f32_row<D>(r, (const float*)a.k, (const float*)a.v, a.n_kv_heads, a.theta, a.scale);
+    hipLaunchKernelGGL(kern, dim3(a.n_items), dim3(64 * NW), lds, s, a);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
 }
 
-template <int D>
-__global__ __launch_bounds__(64) void blockdiag_attn_f32_kernel(const TrBlockDiagArgs a)
+template <int D, int NW, int NS>
+int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
 {
-    const int t = blockIdx.x / a.n_q_heads;
-    const int hq = blockIdx.x % a.n_q_heads;
-    F32Row r;
-    r.q = (const float*)a.q + ((int64_t)t * a.n_q_heads + hq) * D;
-    r.out = (float*)a.out + ((int64_t)t * a.n_q_heads + hq) * D;
-    r.key_lo = a.tok_start[t];
-    r.key_hi = t;
-    r.kvh = hq / a.group;
-    r.pos = (double)(t - r.key_lo);
-    attn_f32_row<D>(r, (const float*)a.k, (const float*)a.v, a.n_kv_heads, a.theta, a.scale);
+    auto kern = blockdiag_attn_kernel<D, NW, NS>;
+    constexpr int lds = smem_bytes<D, NW, NS>();
+    static bool configured = false;
+    if (!configured) {
+        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.n_kv_heads), dim3(64 * NW), lds, s, a);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
 }
 
 } // namespace
 
-int tr_launch_prefix_attn(const TrPrefixArgs& a, int dtype, int head_dim, bool any_split, int total_rows, hipStream_t s)
+// wg_rows: 128 (4 waves, 2-stage ring, two workgroups per CU) or 256 (8 waves, 4-stage ring, one per CU)
+int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool any_split, int total_rows, hipStream_t s)
 {
-    if (dtype == TR_F32) {
-        if (total_rows <= 0) return TR_OK;
-        if (head_dim == 128) hipLaunchKernelGGL(prefix_attn_f32_kernel<128>, dim3(total_rows), dim3(64), 0, s, a);
-        else hipLaunchKernelGGL(prefix_attn_f32_kernel<64>, dim3(total_rows), dim3(64), 0, s, a);
-        TR_HIP(hipGetLastError());
-        return TR_OK;
-    }
     if (a.n_items <= 0) return TR_OK;
-    if (head_dim == 128) hipLaunchKernelGGL(prefix_attn_kernel<128>, dim3(a.n_items), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(prefix_attn_kernel<64>, dim3(a.n_items), dim3(256), 0, s, a);
-    TR_HIP(hipGetLastError());
+    int rc;
+    if (head_dim == 128) rc = wg_rows == 256 ? launch_prefix<128, 8, 4>(a, s) : launch_prefix<128, 4, 2>(a, s);
+    else rc = wg_rows == 256 ? launch_prefix<64, 8, 4>(a, s) : launch_prefix<64, 4, 2>(a, s);
+    if (rc) return rc;
     if (any_split) {
-        const int rows_per_block = 256 / (head_dim / 4);
+        const int rows_per_block = 256 / 32;
         const int blocks = (total_rows + rows_per_block - 1) / rows_per_block;
         if (head_dim == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3(blocks), dim3(256), 0, s, a, total_rows);
         else hipLaunchKernelGGL(combine_kernel<64>, dim3(blocks), dim3(256), 0, s, a, total_rows);
@@ -552,18 +571,9 @@ int tr_launch_prefix_attn(const TrPrefixArgs& a, int dtype, int head_dim, bool a
     return TR_OK;
 }
 
-int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int dtype, int head_dim, hipStream_t s)
+int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s)
 {
     if (a.total_tokens <= 0) return TR_OK;
-    if (dtype == TR_F32) {
-        const int blocks = a.total_tokens * a.n_q_heads;
-        if (head_dim == 128) hipLaunchKernelGGL(blockdiag_attn_f32_kernel<128>, dim3(blocks), dim3(64), 0, s, a);
-        else hipLaunchKernelGGL(blockdiag_attn_f32_kernel<64>, dim3(blocks), dim3(64), 0, s, a);
-    } else {
-        const int blocks = a.n_tiles * a.n_kv_heads;
-        if (head_dim == 128) hipLaunchKernelGGL(blockdiag_attn_kernel<128>, dim3(blocks), dim3(256), 0, s, a);
-        else hipLaunchKernelGGL(blockdiag_attn_kernel<64>, dim3(blocks), dim3(256), 0, s, a);
-    }
-    TR_HIP(hipGetLastError());
-    return TR_OK;
+    if (head_dim == 128) return wg_rows == 256 ? launch_blockdiag<128, 8, 4>(a, s) : launch_blockdiag<128, 4, 2>(a, s);
+    return wg_rows == 256 ? launch_blockdiag<64, 8, 4>(a, s) : launch_blockdiag<64, 4, 2>(a, s);
 }

@@ -99,7 +99,7 @@ struct TrPrefixArgs {
     const int32_t* q_pos;
     void* out;
     float* ws_o;  // [partial rows][head_dim] unnormalised outputs
-    float* ws_ml; // [partial rows][2] running max (raw score units) and sum
+    float* ws_ml; // [partial rows][2] reference maximum (log2 domain) and softmax denominator
     int32_t n_seq;
     int32_t n_items;
     int32_t n_q_heads;
@@ -134,8 +134,10 @@ struct TrBlockDiagArgs {
 // ---- launchers implemented in the .hip files --------------------------------------------------------------
 int tr_launch_assemble(const TrAssembleArgs& a, int dtype, int n_blocks, hipStream_t s);
 int tr_launch_append(const TrAppendArgs& a, int dtype, hipStream_t s);
-int tr_launch_prefix_attn(const TrPrefixArgs& a, int dtype, int head_dim, bool any_split, int total_rows, hipStream_t s);
+int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool any_split, int total_rows, hipStream_t s);
+int tr_launch_prefix_attn_f32(const TrPrefixArgs& a, int head_dim, int total_rows, hipStream_t s);
 int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* theta, hipStream_t s);
 int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int32_t* tok_start,
                         const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s);
-int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int dtype, int head_dim, hipStream_t s);
+int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s);
+int tr_launch_blockdiag_attn_f32(const TrBlockDiagArgs& a, int head_dim, hipStream_t s);
