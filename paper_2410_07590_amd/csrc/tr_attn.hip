@@ -28,6 +28,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -35,7 +36,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define GLB_AS __attribute__((address_space(1)))
 
 constexpr int KT = 64;               // keys per tile
-constexpr float RESCALE_SLACK = 8.f; // log2 units the running maximum may exceed the reference before a rescale
+constexpr float RESCALE_SLACK = 8.f; // log2 units a tile maximum may exceed the reference before a rescale
+constexpr float REREF_BELOW = -32.f; // a row's first visible tile re-references when its maximum is below this
 
 template <int D> struct Geo {
     static constexpr int CPR = D / 8;            // 16-byte chunks per row of one head
@@ -91,7 +93,7 @@ __device__ __forceinline__ int wave_min_i(int v)
 // Q'[row c][16 ks + 8 h .. +7].  Angles are reduced in fp64 to [-1/2, 1/2] revolutions, then v_sin/v_cos.
 template <int D>
 __device__ __forceinline__ void load_q_frags(const __bf16* __restrict__ q, const RowCtx& rc, const double* theta_rev,
-                                             int h, bf16x8 (&qf)[D / 16])
+                                             int h, float sl2e, bf16x8 (&qf)[D / 16])
 {
     // all loads first (one round trip), rows that do not exist read row 0 and are zeroed
     const __bf16* qrow = q + (int64_t)(rc.valid ? rc.orow : 0) * D + 8 * h;
@@ -109,7 +111,8 @@ __device__ __forceinline__ void load_q_frags(const __bf16* __restrict__ q, const
             rev -= rint(rev);
             const float x = (float)rev;
             const float sn = __builtin_amdgcn_sinf(x), cn = __builtin_amdgcn_cosf(x);
-            const float xa = rc.valid ? bf_lo(w[p]) : 0.0f, xb = rc.valid ? bf_hi(w[p]) : 0.0f;
+            // the softmax scale log2(e)/sqrt(d) rides on the query, applied before the single rounding to bf16
+            const float xa = rc.valid ? bf_lo(w[p]) * sl2e : 0.0f, xb = rc.valid ? bf_hi(w[p]) * sl2e : 0.0f;
             f[2 * p] = (__bf16)(xa * cn - xb * sn);
             f[2 * p + 1] = (__bf16)(xb * cn + xa * sn);
         }
@@ -149,15 +152,17 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const _
 // One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.
 template <int D>
 __device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf16x8 (&qf)[D / 16], const RowCtx& rc, int kt,
-                                             bool need_mask, float sl2e, const int (&koff)[D / 16], const int (&voff)[D / 32], int h,
+                                             bool need_mask, const int (&koff)[D / 16], const int (&voff)[D / 32], int h,
                                              Acc<D>& acc)
 {
     using G = Geo<D>;
+    // scores relative to the row reference, in the log2 domain (the queries carry log2(e)/sqrt(d)): the
+    // accumulators start at -mref, so P = exp2(S) needs no further arithmetic
     f32x16 s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[kb][e] = 0.0f;
+        for (int e = 0; e < 16; ++e) s[kb][e] = -acc.mref;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
         const bf16x8 a0 = *(LDS_AS const bf16x8*)(stage + koff[ks]);
@@ -180,39 +185,51 @@ __device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf1
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32)) * sl2e; // both half-waves hold keys of the same query column
-    // lazy reference update (exact: any reference gives the same softmax)
-    const bool grow = mx > acc.mref + RESCALE_SLACK;
-    if (__any(grow)) {
-        // lanes that do not grow keep their reference (alpha = 1; note -inf - -inf would be NaN);
-        // mref = -inf on a row's first visible tile gives alpha = 0, and the accumulators are still 0
-        const float alpha = grow ? __builtin_amdgcn_exp2f(acc.mref - mx) : 1.0f;
-        acc.mref = grow ? mx : acc.mref;
+    mx = fmaxf(mx, __shfl_xor(mx, 32)); // both half-waves hold keys of the same query column
+    // lazy reference update (exact: any reference gives the same softmax).  `first`: nothing accumulated yet and the
+    // tile sits far below the reference - move the reference down so that exp2 does not underflow.
+    const bool first = (acc.l == 0.0f) && (mx < REREF_BELOW) && (mx > -INFINITY);
+    const bool grow = (mx > RESCALE_SLACK) || first;
+    if (__any(grow)) { // rare
+        const float delta = grow ? mx : 0.0f;
+        const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta); // first: accumulators are still zero
+        acc.mref += delta;
         acc.l *= alpha;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc.o[db][e] *= alpha;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[kb][e] -= delta;
     }
-    const float mb = (acc.mref == -INFINITY) ? 0.0f : acc.mref; // nothing visible yet: every p below is exp2(-inf) = 0
-    float lsum = 0.0f;
+    // P = exp2(S), packed to bf16 B-operands; the denominator sums the rounded weights the product uses
+    bf16x8 bpk[2][2];
+    {
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f;
+        ones[1] = (__bf16)1.0f;
+        float l = acc.l;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][e], sl2e, -mb));
-            s[kb][e] = p;
-            lsum += p;
-        }
-    acc.l += lsum;
+            for (int i = 0; i < 8; ++i) {
+                bf16x2 pr;
+                pr[0] = (__bf16)__builtin_amdgcn_exp2f(s[kb][2 * i]);
+                pr[1] = (__bf16)__builtin_amdgcn_exp2f(s[kb][2 * i + 1]);
+                bpk[kb][i / 4][2 * (i % 4)] = pr[0];
+                bpk[kb][i / 4][2 * (i % 4) + 1] = pr[1];
+                l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l, false);
+            }
+        acc.l = l;
+    }
     // O^T += V^T P^T.  k-slot j of k-step (kb, t) is key 32 kb + 16 t + 8 (j >> 2) + 4 h + (j & 3).
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            bf16x8 bp;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) bp[e] = (__bf16)s[kb][8 * t + e];
+            const bf16x8 bp = bpk[kb][t];
             const int rbase = G::TILE_BYTES + (32 * kb + 16 * t) * D * 2;
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
@@ -231,7 +248,7 @@ __device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf1
 template <int D, int NW, int NS>
 __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const __bf16* __restrict__ v, int n_kv_heads,
                                            int kvh, const RowCtx& rc, const bf16x8 (&qf)[D / 16], int kt_begin,
-                                           int kt_end, int key_clamp, int mask_hi_min, int mask_lo_max, float sl2e,
+                                           int kt_end, int key_clamp, int mask_hi_min, int mask_lo_max,
                                            LDS_AS char* smem, Acc<D>& acc)
 {
     using G = Geo<D>;
@@ -280,7 +297,7 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
         if (active) {
             LDS_AS const char* stage = smem + (t % NS) * G::STAGE_BYTES;
             const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
-            compute_tile<D>(stage, qf, rc, kt, need_mask, sl2e, koff, voff, h, acc);
+            compute_tile<D>(stage, qf, rc, kt, need_mask, koff, voff, h, acc);
         }
     }
 }
@@ -369,18 +386,18 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     const int kt_end = min(se, sd.kv_row0 + n_doc + last_tok + 1);
 
     bf16x8 qf[D / 16];
-    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, qf);
+    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, a.scale_log2e, qf);
 
     Acc<D> acc;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc.o[db][e] = 0.0f;
-    acc.mref = -INFINITY;
+    acc.mref = 0.0f;
     acc.l = 0.0f;
 
     attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, kt_begin, kt_end,
-                          sd.kv_row0 + sd.kv_len - 1, sd.kv_row0 + n_doc + first_tok, sd.kv_row0, a.scale_log2e, smem, acc);
+                          sd.kv_row0 + sd.kv_len - 1, sd.kv_row0 + n_doc + first_tok, sd.kv_row0, smem, acc);
 
     const float l_tot = acc.l + __shfl_xor(acc.l, 32);
     __builtin_amdgcn_s_barrier(); // all waves are done with the K/V stages; reuse them as store staging
@@ -391,7 +408,8 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
         const int rows_s = sd.n_q * g;
         const int64_t prow = (int64_t)sd.ws_row0 + (int64_t)(split * a.n_kv_heads + kvh) * rows_s + tok_local * g + rl % g;
         store_rows<D, true>(acc, l_tot, rc.valid, prow, a.ws_o, wave_buf, lane);
-        if (rc.valid && h == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(acc.mref, l_tot);
+        // a split in which the row saw no key reports m = -inf so that the merge ignores it
+        if (rc.valid && h == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(l_tot > 0.0f ? acc.mref : -INFINITY, l_tot);
     }
 }
 
@@ -439,18 +457,28 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
     for (int e = 0; e < CPLN; ++e) acc[e] = 0.0f;
     const float* base = a.ws_o + prow0 * D + CPLN * lane_r;
     const int row_lane0 = threadIdx.x & 32; // first lane of this row's half-wave
-    for (int sp = 0; sp < sd.n_split; ++sp) {
-        const float w = __shfl(w_i, row_lane0 + sp);
-        const float* p = base + sp * pstride * D;
-        if (CPLN == 4) {
-            const f32x4 x = *(const f32x4*)p;
+    // four splits per round so that four loads are in flight (the loop count is a run-time value)
+    for (int sp0 = 0; sp0 < sd.n_split; sp0 += 4) {
+        f32x4 x[4];
+        float w[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] += w * x[e];
-        } else {
-            const float2 x = *(const float2*)p;
-            acc[0] += w * x.x;
-            acc[1] += w * x.y;
+        for (int u = 0; u < 4; ++u) {
+            const int sp = sp0 + u;
+            const bool ok = sp < sd.n_split;
+            const float* p = base + (int64_t)(ok ? sp : 0) * pstride * D;
+            if (CPLN == 4) {
+                x[u] = *(const f32x4*)p;
+            } else {
+                const float2 t = *(const float2*)p;
+                x[u][0] = t.x; x[u][1] = t.y; x[u][2] = 0.0f; x[u][3] = 0.0f;
+            }
+            const float ws = __shfl(w_i, row_lane0 + (ok ? sp : 0));
+            w[u] = ok ? ws : 0.0f;
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < CPLN; ++e) acc[e] += w[u] * x[u][e];
     }
     const float inv = 1.0f / L;
     __bf16* op = (__bf16*)a.out + ((int64_t)tq * a.n_q_heads + hq) * D + CPLN * lane_r;
@@ -495,18 +523,18 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     const int lo_last = a.tok_start[t_last];
 
     bf16x8 qf[D / 16];
-    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, qf);
+    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, a.scale_log2e, qf);
 
     Acc<D> acc;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc.o[db][e] = 0.0f;
-    acc.mref = -INFINITY;
+    acc.mref = 0.0f;
     acc.l = 0.0f;
 
     attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, lo_first, t_last + 1, T - 1,
-                          t_first, lo_last, a.scale_log2e, smem, acc);
+                          t_first, lo_last, smem, acc);
 
     const float l_tot = acc.l + __shfl_xor(acc.l, 32);
     __builtin_amdgcn_s_barrier();
