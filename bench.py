@@ -66,6 +66,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--no-extra", action="store_true", help="skip configurations 4/5 and the CPU baseline")
     ap.add_argument("--no-graph", action="store_true", help="time the eager loop instead of a HIP graph replay")
+    ap.add_argument("--case", default=None,
+                    help="profiling aid: run only one kernel path --iters times, eagerly, and print nothing but a note "
+                         "(step2, assemble2, attn2, assemble4, attn4, offline5, copy)")
+    ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -83,6 +87,9 @@ def main():
         sys.exit(1)
     B.lib()
     torch.cuda.set_device(0)
+    if args.case:
+        run_case(torch, B, synth, args.case, args.iters)
+        return
 
     # ------------------------------------------------------------------ configuration 2 workload
     cfg = synth.CONFIGS[2]
@@ -207,6 +214,58 @@ def main():
         result["cpu_baseline"] = cpu_baseline(synth, cfg)
     result["roofline_extra"] = roof_extra
     print(json.dumps(result))
+
+
+def run_case(torch, B, synth, case, iters):
+    """One kernel path, a few eager launches: what the rocprofv3 counter runs under profiles/ execute."""
+    if case == "copy":
+        # calibration for the HBM counters: a plain device copy of known size (256 MiB read, 256 MiB written)
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(iters):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print("case copy: %d launches of a %d-byte device copy" % (iters, src.numel()))
+        return
+    if case == "offline5":
+        cfg = synth.CONFIGS[5]
+        sh = cfg.shape
+        gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+        pc = synth.make_packed_chunks(cfg)
+        q, k, v = pc.q.cuda(), pc.k.cuda(), pc.v.cuda()
+        cu = torch.from_numpy(pc.cu).cuda()
+        max_len = int(np.diff(pc.cu).max())
+        out, k_rot = torch.empty_like(q), torch.empty_like(k)
+        ws = B.workspace(B.tr_chunk_prefill_attn_workspace_size(gs, q.shape[0], max_len))
+        for _ in range(iters):
+            B.tr_chunk_prefill_attn(gs, q, k, v, cu, pc.cu.size - 1, max_len, out, k_rot, ws)
+        torch.cuda.synchronize()
+        print("case offline5: %d calls" % iters)
+        return
+    cfg = synth.CONFIGS[int(case[-1])]
+    sh = cfg.shape
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    store = synth.make_store(cfg)
+    sd = B.Store(gs, store.k.cuda(), store.v.cuda(), store.row_start)
+    req = synth.make_requests(cfg, store)[0]
+    offsets, _ = B.tr_plan(sd, req.chunk_ids, req.pos_mode, want_pos_ids=False)
+    n_doc, kv_len = int(offsets[-1]), int(offsets[-1]) + req.n_q
+    ck = torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda")
+    cv = torch.empty_like(ck)
+    q, k_q, v_q = req.q.cuda(), req.k_q.cuda(), req.v_q.cuda()
+    q_pos = torch.from_numpy(req.q_pos).cuda()
+    out = torch.empty_like(q)
+    ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, req.n_q, kv_len))
+    asm = lambda: B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
+    app = lambda: B.tr_kv_append(gs, k_q, v_q, q_pos, ck, cv, n_doc)
+    att = lambda: B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
+    asm(); app()
+    what = {"assemble": [asm], "attn": [att], "step": [asm, app, att]}[case[:-1]]
+    for _ in range(iters):
+        for f in what:
+            f()
+    torch.cuda.synchronize()
+    print("case %s: %d iterations" % (case, iters))
 
 
 def bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof):
