@@ -27,7 +27,13 @@ N_VARIANTS = 16
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters read
 # on a copy kernel of known size (see profiles/ and the design doc).  None where not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 43267266,       # prefix_attn 26.0 MB (15.8 MB of split partials written) + combine 17.2 MB
+    ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16899349,
+    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268636206,
+    ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 208421815,  # prefix_attn 171.7 MB + combine 36.7 MB
+    ("tr_chunk_prefill_attn", "offline-64x512"): 808238715,    # table 0.6 MB + key rotation 135.3 MB + attention 672.3 MB
+}
 
 
 def _events(torch, n):

@@ -1,0 +1,285 @@
+"""Host side of the C ABI, no GPU needed: the library loads, exports what include/turborag.h declares, computes
+the gather plan bit-exactly, and turns every invalid call into an error code before anything is enqueued.
+
+Device pointers handed to the library here are made-up non-null addresses: every call below either fails
+validation or is a documented no-op, so none of them is ever dereferenced or passed to a kernel.
+"""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2410_07590_amd import binding as B
+from paper_2410_07590_amd import build as trbuild
+from paper_2410_07590_amd import synth
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "turborag.h")
+FAKE = C.c_void_p(0x7000_0000_1000)   # 256-byte aligned, never touched
+FAKE2 = C.c_void_p(0x7000_0100_0000)
+
+
+@pytest.fixture(scope="module")
+def L():
+    if trbuild.needs_build():
+        trbuild.build()
+    return B.lib()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tr_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_and_library_exports_the_same_symbols(L):
+    declared = _declared_functions()
+    assert len(declared) >= 14
+    for name in declared:
+        assert hasattr(L, name), "library does not export %s" % name
+    assert sorted(B.EXPORTS) == declared
+
+
+def test_status_codes_match_header():
+    text = open(HEADER).read()
+    for name in ["TR_OK", "TR_ERR_INVALID_ARG", "TR_ERR_BAD_CHUNK_ID", "TR_ERR_BAD_PLAN", "TR_ERR_SHAPE",
+                 "TR_ERR_UNSUPPORTED", "TR_ERR_HIP", "TR_ERR_WORKSPACE", "TR_POS_COMPOSITE", "TR_POS_REORDERED",
+                 "TR_F32", "TR_BF16", "TR_ROPE_INTERLEAVED", "TR_ROPE_HALF"]:
+        m = re.search(r"\b%s\s*=\s*(-?\d+)" % name, text)
+        assert m, name
+        assert getattr(B, name) == int(m.group(1)), name
+
+
+def _shape(hq=28, hkv=4, d=128, dtype=B.TR_BF16, base=1e6, layout=B.TR_ROPE_INTERLEAVED):
+    return B.tr_shape(hq, hkv, d, dtype, float(base), layout, 0)
+
+
+def _store(L, shape, row_start):
+    rs = np.ascontiguousarray(row_start, dtype=np.int64)
+    h = C.c_void_p(0)
+    rc = L.tr_store_create(C.byref(shape), FAKE, FAKE2, rs.ctypes.data_as(C.c_void_p), C.c_int32(rs.size - 1), C.byref(h))
+    return rc, h
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def _i64(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def test_shape_validation(L):
+    bad = [(_shape(hq=28, hkv=5), B.TR_ERR_SHAPE), (_shape(d=96), B.TR_ERR_SHAPE), (_shape(hq=0), B.TR_ERR_SHAPE),
+           (_shape(dtype=7), B.TR_ERR_SHAPE), (_shape(layout=B.TR_ROPE_HALF), B.TR_ERR_UNSUPPORTED),
+           (_shape(base=0.0), B.TR_ERR_SHAPE)]
+    for sh, want in bad:
+        rc, h = _store(L, sh, [0, 4])
+        assert rc == want, (rc, want, L.tr_last_error())
+        assert L.tr_last_error() != b""
+    rc, h = _store(L, _shape(), [0, 4])
+    assert rc == B.TR_OK
+    assert L.tr_store_destroy(h) == B.TR_OK
+
+
+def test_store_create_validation(L):
+    sh = _shape()
+    assert _store(L, sh, [0, 8, 4])[0] == B.TR_ERR_INVALID_ARG          # row starts must not decrease
+    assert _store(L, sh, [1, 8])[0] in (B.TR_OK, B.TR_ERR_INVALID_ARG)    # a base offset is the caller's business
+    h = C.c_void_p(0)
+    rs, rs_p = _i64([0, 4])
+    assert L.tr_store_create(C.byref(sh), None, FAKE2, rs_p, C.c_int32(1), C.byref(h)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_store_create(C.byref(sh), FAKE, FAKE2, None, C.c_int32(1), C.byref(h)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_store_create(C.byref(sh), FAKE, FAKE2, rs_p, C.c_int32(-1), C.byref(h)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_store_create(C.byref(sh), FAKE, FAKE2, rs_p, C.c_int32(1), None) == B.TR_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4])
+@pytest.mark.parametrize("pos_mode", [B.TR_POS_COMPOSITE, B.TR_POS_REORDERED])
+def test_plan_is_bit_exact_against_the_oracle(L, cfg_id, pos_mode):
+    """Sec. 3.2: offsets, and position ids under both schemes, for the chunk-length mix of each configuration."""
+    cfg = synth.CONFIGS[cfg_id]
+    lens = synth.chunk_lengths(cfg)
+    row_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rc, h = _store(L, _shape(cfg.shape.n_q_heads, cfg.shape.n_kv_heads, cfg.shape.head_dim), row_start)
+    assert rc == B.TR_OK
+    rng = np.random.default_rng(cfg_id)
+    ids = rng.integers(0, lens.size, size=min(10, lens.size) + 3).astype(np.int32)   # duplicates allowed
+    ids_a, ids_p = _i32(ids)
+    off = np.full(ids.size + 1, -1, np.int64)
+    assert L.tr_plan(h, ids_p, C.c_int32(ids.size), C.c_int32(pos_mode), off.ctypes.data_as(C.c_void_p), None, C.c_int64(0)) == B.TR_OK
+    pos = np.full(int(off[-1]), -1, np.int32)
+    assert L.tr_plan(h, ids_p, C.c_int32(ids.size), C.c_int32(pos_mode), off.ctypes.data_as(C.c_void_p),
+                     pos.ctypes.data_as(C.c_void_p), C.c_int64(pos.size)) == B.TR_OK
+    want_off, want_delta, want_pos = oracle.plan(row_start, ids, pos_mode)
+    assert off.dtype == want_off.dtype and np.array_equal(off, want_off)
+    assert np.array_equal(pos, want_pos)
+    # capacity one short: error, not a partial write
+    if pos.size:
+        assert L.tr_plan(h, ids_p, C.c_int32(ids.size), C.c_int32(pos_mode), off.ctypes.data_as(C.c_void_p),
+                         pos.ctypes.data_as(C.c_void_p), C.c_int64(pos.size - 1)) == B.TR_ERR_BAD_PLAN
+    L.tr_store_destroy(h)
+
+
+def test_plan_errors(L):
+    rc, h = _store(L, _shape(), [0, 4, 9, 9, 20])
+    assert rc == B.TR_OK
+    off = np.zeros(8, np.int64)
+    off_p = off.ctypes.data_as(C.c_void_p)
+    for bad in ([0, 4], [-1, 0], [1, 2, 3, 99]):
+        a, p = _i32(bad)
+        assert L.tr_plan(h, p, C.c_int32(a.size), C.c_int32(B.TR_POS_REORDERED), off_p, None, C.c_int64(0)) == B.TR_ERR_BAD_CHUNK_ID
+        assert b"chunk" in L.tr_last_error()
+    a, p = _i32([0, 1])
+    assert L.tr_plan(None, p, C.c_int32(2), C.c_int32(0), off_p, None, C.c_int64(0)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_plan(h, None, C.c_int32(2), C.c_int32(0), off_p, None, C.c_int64(0)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_plan(h, p, C.c_int32(2), C.c_int32(0), None, None, C.c_int64(0)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_plan(h, p, C.c_int32(-2), C.c_int32(0), off_p, None, C.c_int64(0)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_plan(h, p, C.c_int32(2), C.c_int32(5), off_p, None, C.c_int64(0)) == B.TR_ERR_INVALID_ARG
+    # empty request and empty chunk are legal
+    assert L.tr_plan(h, p, C.c_int32(0), C.c_int32(0), off_p, None, C.c_int64(0)) == B.TR_OK and off[0] == 0
+    a, p = _i32([2, 2])
+    assert L.tr_plan(h, p, C.c_int32(2), C.c_int32(1), off_p, None, C.c_int64(0)) == B.TR_OK
+    assert list(off[:3]) == [0, 0, 0]
+    L.tr_store_destroy(h)
+
+
+def test_assemble_validation_happens_before_any_enqueue(L):
+    rc, h = _store(L, _shape(), [0, 4, 9, 9, 20])
+    assert rc == B.TR_OK
+    ids, ids_p = _i32([1, 3, 0])
+    good, good_p = _i64([0, 5, 16, 20])
+
+    def call(ids_p=ids_p, off_p=good_p, n=3, mode=B.TR_POS_REORDERED, k=FAKE, v=FAKE2, cap=64, store=h):
+        return L.tr_kv_assemble(store, ids_p, off_p, C.c_int32(n), C.c_int32(mode), k, v, C.c_int64(cap), None)
+
+    assert call(cap=19) == B.TR_ERR_BAD_PLAN                       # does not fit
+    bad, bad_p = _i64([0, 5, 15, 20])
+    assert call(off_p=bad_p) == B.TR_ERR_BAD_PLAN                  # not the prefix sum of the lengths
+    bad2, bad2_p = _i64([1, 6, 17, 21])
+    assert call(off_p=bad2_p) == B.TR_ERR_BAD_PLAN                 # must start at 0
+    ids_bad, ids_bad_p = _i32([1, 4, 0])
+    assert call(ids_p=ids_bad_p) == B.TR_ERR_BAD_CHUNK_ID
+    assert call(k=None) == B.TR_ERR_INVALID_ARG
+    assert call(v=None) == B.TR_ERR_INVALID_ARG
+    assert call(store=None) == B.TR_ERR_INVALID_ARG
+    assert call(n=-1) == B.TR_ERR_INVALID_ARG
+    assert call(mode=2) == B.TR_ERR_INVALID_ARG
+    assert call(n=0) == B.TR_OK                                     # no chunks: nothing to do, nothing enqueued
+    e_ids, e_ids_p = _i32([2])
+    e_off, e_off_p = _i64([0, 0])
+    assert call(ids_p=e_ids_p, off_p=e_off_p, n=1) == B.TR_OK       # one empty chunk: nothing to move
+    L.tr_store_destroy(h)
+
+
+def test_assemble_batched_validation(L):
+    rc, h = _store(L, _shape(), [0, 4, 9, 9, 20])
+    ids, ids_p = _i32([1, 3, 0, 0])
+    cu, cu_p = _i32([0, 3, 4])
+    pm, pm_p = _i32([1, 0])
+    rows, rows_p = _i64([0, 24, 30])       # request 0: 20 doc rows + 4 query rows; request 1: 4 + 2
+
+    def call(ids_p=ids_p, cu_p=cu_p, pm_p=pm_p, rows_p=rows_p, n=2, cap=30):
+        return L.tr_kv_assemble_batched(h, ids_p, cu_p, pm_p, rows_p, C.c_int32(n), FAKE, FAKE2, C.c_int64(cap), None)
+
+    assert call(cap=29) == B.TR_ERR_BAD_PLAN
+    small, small_p = _i64([0, 19, 30])
+    assert call(rows_p=small_p) == B.TR_ERR_BAD_PLAN               # request 0's documents do not fit its rows
+    badcu, badcu_p = _i32([0, 3, 2])
+    assert call(cu_p=badcu_p) == B.TR_ERR_INVALID_ARG
+    badpm, badpm_p = _i32([1, 3])
+    assert call(pm_p=badpm_p) == B.TR_ERR_INVALID_ARG
+    badid, badid_p = _i32([1, 3, 0, 7])
+    assert call(ids_p=badid_p) == B.TR_ERR_BAD_CHUNK_ID
+    assert call(n=0) == B.TR_OK
+    L.tr_store_destroy(h)
+
+
+def test_append_validation(L):
+    sh = _shape()
+
+    def call(n_q=4, dst=16, cap=20, k=FAKE, qpos=FAKE, ck=FAKE2, shape=sh):
+        return L.tr_kv_append(C.byref(shape), k, FAKE, qpos, C.c_int32(n_q), ck, FAKE2, C.c_int64(dst), C.c_int64(cap), None)
+
+    assert call(cap=19) == B.TR_ERR_BAD_PLAN
+    assert call(dst=-1) == B.TR_ERR_INVALID_ARG
+    assert call(n_q=-1) == B.TR_ERR_INVALID_ARG
+    assert call(k=None) == B.TR_ERR_INVALID_ARG
+    assert call(qpos=None) == B.TR_ERR_INVALID_ARG
+    assert call(shape=_shape(d=100)) == B.TR_ERR_SHAPE
+    assert call(n_q=0) == B.TR_OK
+
+
+def test_prefill_attn_validation_and_workspace(L):
+    sh = _shape()
+    size = L.tr_prefill_attn_workspace_size(C.byref(sh), C.c_int32(64), C.c_int64(4160))
+    assert size > 0 and size % 256 == 0
+    # a long query over few keys fills the chip without splitting: no workspace needed
+    assert L.tr_prefill_attn_workspace_size(C.byref(sh), C.c_int32(4096), C.c_int64(4096)) == 0
+    # fp32 path never splits
+    assert L.tr_prefill_attn_workspace_size(C.byref(_shape(4, 4, 64, B.TR_F32, 1e4)), C.c_int32(16), C.c_int64(144)) == 0
+
+    def call(n_q=64, kv_len=4160, ws=FAKE2, ws_bytes=size, q=FAKE, out=FAKE, shape=sh):
+        return L.tr_prefill_attn(C.byref(shape), q, FAKE, FAKE, FAKE, C.c_int32(n_q), C.c_int64(kv_len), out, ws,
+                                 C.c_size_t(ws_bytes), None)
+
+    assert call(kv_len=63) == B.TR_ERR_INVALID_ARG                 # fewer cache rows than query tokens
+    assert call(q=None) == B.TR_ERR_INVALID_ARG
+    assert call(out=None) == B.TR_ERR_INVALID_ARG
+    assert call(n_q=-1) == B.TR_ERR_INVALID_ARG
+    assert call(ws=None, ws_bytes=0) == B.TR_ERR_WORKSPACE
+    assert call(ws_bytes=size - 1) == B.TR_ERR_WORKSPACE
+    assert call(ws=C.c_void_p(FAKE2.value + 16)) == B.TR_ERR_WORKSPACE
+    assert b"aligned" in L.tr_last_error()
+    assert call(shape=_shape(hq=30)) == B.TR_ERR_SHAPE
+    assert call(n_q=0, kv_len=100) == B.TR_OK
+
+
+def test_prefill_attn_batched_validation(L):
+    sh = _shape()
+    cu, cu_p = _i32([0, 40, 100])
+    rows, rows_p = _i64([0, 3000, 7000])
+    size = L.tr_prefill_attn_batched_workspace_size(C.byref(sh), cu_p, rows_p, C.c_int32(2))
+    assert size > 0
+
+    def call(cu_p=cu_p, rows_p=rows_p, n=2, ws=FAKE2, ws_bytes=size):
+        return L.tr_prefill_attn_batched(C.byref(sh), FAKE, FAKE, FAKE, FAKE, cu_p, rows_p, C.c_int32(n), FAKE, ws,
+                                         C.c_size_t(ws_bytes), None)
+
+    short, short_p = _i64([0, 30, 7000])        # request 0 has 40 query tokens but 30 cache rows
+    assert call(rows_p=short_p) == B.TR_ERR_INVALID_ARG
+    badcu, badcu_p = _i32([0, 50, 40])
+    assert call(cu_p=badcu_p) == B.TR_ERR_INVALID_ARG
+    assert call(ws_bytes=size // 2) == B.TR_ERR_WORKSPACE
+    assert call(n=-1) == B.TR_ERR_INVALID_ARG
+    assert call(n=0) == B.TR_OK
+
+
+def test_chunk_prefill_validation(L):
+    sh = _shape(32, 8, 128, B.TR_BF16, 5e5)
+    size = L.tr_chunk_prefill_attn_workspace_size(C.byref(sh), C.c_int64(32768), C.c_int32(512))
+    assert size > 0 and size % 256 == 0
+
+    def call(n_chunks=64, total=32768, max_len=512, ws=FAKE2, ws_bytes=size, krot=FAKE, cu=FAKE, shape=sh):
+        return L.tr_chunk_prefill_attn(C.byref(shape), FAKE, FAKE, FAKE, cu, C.c_int32(n_chunks), C.c_int64(total),
+                                       C.c_int32(max_len), FAKE, krot, ws, C.c_size_t(ws_bytes), None)
+
+    assert call(krot=None) == B.TR_ERR_INVALID_ARG                  # the rotated keys are the attention kernel's input
+    assert call(cu=None) == B.TR_ERR_INVALID_ARG
+    assert call(ws=None, ws_bytes=0) == B.TR_ERR_WORKSPACE
+    assert call(ws_bytes=size - 256) == B.TR_ERR_WORKSPACE
+    assert call(max_len=0) == B.TR_ERR_INVALID_ARG
+    assert call(n_chunks=-1) == B.TR_ERR_INVALID_ARG
+    assert call(shape=_shape(32, 8, 128, B.TR_BF16, 5e5, B.TR_ROPE_HALF)) == B.TR_ERR_UNSUPPORTED
+    assert call(total=0, n_chunks=0) == B.TR_OK
+
+
+def test_binding_raises_with_the_library_message(L):
+    sh = B.make_shape(28, 4, 96, "bf16", 1e6)
+    with pytest.raises(B.TurboRagError) as e:
+        B.Store(sh, None, None, np.array([0, 4]))
+    assert e.value.code in (B.TR_ERR_SHAPE, B.TR_ERR_INVALID_ARG)
