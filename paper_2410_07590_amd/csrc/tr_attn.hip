@@ -89,33 +89,90 @@ __device__ __forceinline__ int wave_min_i(int v)
     return __builtin_amdgcn_readfirstlane(v);
 }
 
-// Rotated query fragments (Eq. 3 at the token's position id): lane (c = lane & 31, h = lane >> 5) holds
-// Q'[row c][16 ks + 8 h .. +7].  Angles are reduced in fp64 to [-1/2, 1/2] revolutions, then v_sin/v_cos.
+// ---- rotated queries (Eq. 3 at the token's position id) -------------------------------------------------------
+// Lane (c = lane & 31, h = lane >> 5) ends up holding Q'[row c][16 ks + 8 h .. +7] for ks < D/16, scaled by
+// log2(e)/sqrt(d) before its single rounding to bf16.  Angles are reduced in fp64 to [-1/2, 1/2] revolutions and
+// then go through v_sin/v_cos, which take revolutions.
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int ROT_SLOTS = 8; // distinct tokens a wave's 32 packed rows can span when the GQA group is >= 4
+
+// Issue the loads of this lane's raw fragments; rows that do not exist read row 0 and are zeroed later.
 template <int D>
-__device__ __forceinline__ void load_q_frags(const __bf16* __restrict__ q, const RowCtx& rc, const double* theta_rev,
-                                             int h, float sl2e, bf16x8 (&qf)[D / 16])
+__device__ __forceinline__ void load_q_raw(const __bf16* __restrict__ q, const RowCtx& rc, int h, u32x4 (&raw)[D / 16])
 {
-    // all loads first (one round trip), rows that do not exist read row 0 and are zeroed
     const __bf16* qrow = q + (int64_t)(rc.valid ? rc.orow : 0) * D + 8 * h;
-    uint4 raw[D / 16];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) raw[ks] = *(const uint4*)(qrow + 16 * ks);
+    for (int ks = 0; ks < D / 16; ++ks) raw[ks] = *(const u32x4*)(qrow + 16 * ks);
+}
+
+__device__ __forceinline__ void rot_pair(uint32_t w, float cn, float sn, float sl2e, bool valid, bf16x8& f, int p)
+{
+    const float xa = valid ? bf_lo(w) * sl2e : 0.0f, xb = valid ? bf_hi(w) * sl2e : 0.0f;
+    f[2 * p] = (__bf16)(xa * cn - xb * sn);
+    f[2 * p + 1] = (__bf16)(xb * cn + xa * sn);
+}
+
+// Every lane computes the angles of its own row: used when rows of a wave share few tokens (group < 4).
+template <int D>
+__device__ __forceinline__ void rotate_q_direct(const u32x4 (&raw)[D / 16], double pos, const double* theta_rev, int h,
+                                                bool valid, float sl2e, bf16x8 (&qf)[D / 16])
+{
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
         bf16x8 f;
-        const uint32_t w[4] = {raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w};
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const double t0 = theta_rev[8 * ks + p], t1 = theta_rev[8 * ks + 4 + p];
-            double rev = rc.pos * (h ? t1 : t0);
+            double rev = pos * (h ? t1 : t0);
             rev -= rint(rev);
             const float x = (float)rev;
-            const float sn = __builtin_amdgcn_sinf(x), cn = __builtin_amdgcn_cosf(x);
-            // the softmax scale log2(e)/sqrt(d) rides on the query, applied before the single rounding to bf16
-            const float xa = rc.valid ? bf_lo(w[p]) * sl2e : 0.0f, xb = rc.valid ? bf_hi(w[p]) * sl2e : 0.0f;
-            f[2 * p] = (__bf16)(xa * cn - xb * sn);
-            f[2 * p + 1] = (__bf16)(xb * cn + xa * sn);
+            rot_pair(raw[ks][p], __builtin_amdgcn_cosf(x), __builtin_amdgcn_sinf(x), sl2e, valid, f, p);
         }
+        qf[ks] = f;
+    }
+}
+
+// The g query heads of a token share its angles, so a wave's 32 rows need at most ROT_SLOTS x D/2 distinct
+// (cos, sin) pairs instead of 32 x D/2: the wave computes them once into a private LDS table, lane -> pair index,
+// one token slot (two for D = 64) per pass.  pos_lane: position id of slot (lane & 7).
+// Table layout: slot j, pair m at byte j * 4 D + (((m >> 1) ^ 2 j) * 16) + (m & 1) * 8.
+template <int D>
+__device__ __forceinline__ void build_rot_table(LDS_AS char* tab, double th /* theta_rev[lane % (D/2)] */, int lane, int pos_lane)
+{
+    constexpr int PAIRS = D / 2, LPS = 64 / PAIRS;
+    const int m = lane % PAIRS;
+#pragma unroll
+    for (int pass = 0; pass < ROT_SLOTS / LPS; ++pass) {
+        const int j = pass * LPS + lane / PAIRS;
+        double rev = (double)__shfl(pos_lane, j) * th;
+        rev -= rint(rev);
+        const float x = (float)rev;
+        f32x2 cs;
+        cs[0] = __builtin_amdgcn_cosf(x);
+        cs[1] = __builtin_amdgcn_sinf(x);
+        *(LDS_AS f32x2*)(tab + j * (4 * D) + (((m >> 1) ^ (2 * j)) * 16) + (m & 1) * 8) = cs;
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void rotate_q_shared(const u32x4 (&raw)[D / 16], LDS_AS const char* tab, int slot, int h,
+                                                bool valid, float sl2e, bf16x8 (&qf)[D / 16])
+{
+    LDS_AS const char* row = tab + slot * (4 * D);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+        // pairs 8 ks + 4 h .. +3 = 16-byte chunks 2 u, 2 u + 1 with u = 2 ks + h
+        const int ch = (2 * (2 * ks + h)) ^ (2 * slot);
+        const f32x4 cs0 = *(LDS_AS const f32x4*)(row + ch * 16);
+        const f32x4 cs1 = *(LDS_AS const f32x4*)(row + ch * 16 + 16);
+        bf16x8 f;
+        rot_pair(raw[ks][0], cs0[0], cs0[1], sl2e, valid, f, 0);
+        rot_pair(raw[ks][1], cs0[2], cs0[3], sl2e, valid, f, 1);
+        rot_pair(raw[ks][2], cs1[0], cs1[1], sl2e, valid, f, 2);
+        rot_pair(raw[ks][3], cs1[2], cs1[3], sl2e, valid, f, 3);
         qf[ks] = f;
     }
 }
@@ -242,13 +299,43 @@ __device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf1
         }
 }
 
-// The tile loop shared by both kernels.  kt_begin..kt_end: cache rows this workgroup walks (workgroup-uniform);
-// key_clamp: last row that may be loaded; tile [kt, kt+64) needs per-element masking iff
+// The rows of K/V one workgroup walks: tiles of 64 keys from kt_begin, n_tiles of them; key_clamp is the last row
+// that may be loaded (rows past it are never visible and read that row instead).
+struct Walk {
+    int kt_begin;
+    int n_tiles;
+    int key_clamp;
+    int head_off;
+    int64_t row_elems;
+};
+
+__device__ __forceinline__ Walk make_walk(int kt_begin, int kt_end, int key_clamp, int n_kv_heads, int kvh, int d)
+{
+    Walk w;
+    w.kt_begin = kt_begin;
+    w.n_tiles = kt_end > kt_begin ? (kt_end - kt_begin + KT - 1) / KT : 0;
+    w.key_clamp = key_clamp;
+    w.head_off = kvh * d;
+    w.row_elems = (int64_t)n_kv_heads * d;
+    return w;
+}
+
+// Tiles 0 .. NS-2 in flight.  Stage NS-1 stays free until the tile loop's first iteration has passed its barrier.
+template <int D, int NW, int NS>
+__device__ __forceinline__ void issue_prologue(const __bf16* __restrict__ k, const __bf16* __restrict__ v, const Walk& w,
+                                               LDS_AS char* smem, int wave, int lane)
+{
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < w.n_tiles)
+            issue_tile<D, NW>(k, v, w.row_elems, w.head_off, w.kt_begin + p * KT, w.key_clamp, smem + p * Geo<D>::STAGE_BYTES, wave, lane);
+}
+
+// The tile loop shared by both kernels (issue_prologue has run).  Tile [kt, kt+64) needs per-element masking iff
 // kt+63 > mask_hi_min or kt < mask_lo_max.
 template <int D, int NW, int NS>
-__device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const __bf16* __restrict__ v, int n_kv_heads,
-                                           int kvh, const RowCtx& rc, const bf16x8 (&qf)[D / 16], int kt_begin,
-                                           int kt_end, int key_clamp, int mask_hi_min, int mask_lo_max,
+__device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const __bf16* __restrict__ v, const Walk& w,
+                                           const RowCtx& rc, const bf16x8 (&qf)[D / 16], int mask_hi_min, int mask_lo_max,
                                            LDS_AS char* smem, Acc<D>& acc)
 {
     using G = Geo<D>;
@@ -273,17 +360,9 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
             voff[db] = r * D * 2 + (4 * (db ^ G::vswz(r)) + 2 * colhalf + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
     }
 
-    const int64_t row_elems = (int64_t)n_kv_heads * D;
-    const int head_off = kvh * D;
-    const int n_tiles = kt_end > kt_begin ? (kt_end - kt_begin + KT - 1) / KT : 0;
-
-    // prologue: tiles 0 .. NS-2 in flight
-#pragma unroll
-    for (int p = 0; p < NS - 1; ++p)
-        if (p < n_tiles) issue_tile<D, NW>(k, v, row_elems, head_off, kt_begin + p * KT, key_clamp, smem + p * G::STAGE_BYTES, wave, lane);
-
+    const int n_tiles = w.n_tiles;
     for (int t = 0; t < n_tiles; ++t) {
-        const int kt = kt_begin + t * KT;
+        const int kt = w.kt_begin + t * KT;
         // tile t has landed once at most the loads of the tiles issued after it are outstanding
         const int later = min(NS - 2, n_tiles - 1 - t);
         if (NS >= 4 && later >= 2) wait_vm<2 * IPW>();
@@ -291,7 +370,7 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
         else wait_vm<0>();
         __builtin_amdgcn_s_barrier(); // every wave's share of tile t is in LDS; everyone is done with tile t-1
         if (t + NS - 1 < n_tiles)
-            issue_tile<D, NW>(k, v, row_elems, head_off, kt + (NS - 1) * KT, key_clamp,
+            issue_tile<D, NW>(k, v, w.row_elems, w.head_off, kt + (NS - 1) * KT, w.key_clamp,
                               smem + ((t + NS - 1) % NS) * G::STAGE_BYTES, wave, lane);
         const bool active = (kt <= wave_hi_max) && (kt + KT - 1 >= wave_lo_min); // wave-uniform
         if (active) {
@@ -299,6 +378,34 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
             const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
             compute_tile<D>(stage, qf, rc, kt, need_mask, koff, voff, h, acc);
         }
+    }
+}
+
+// Raw query loads, the first K/V tiles, then the rotation: the tile loads fly while the angles are computed.
+// Every ordinary load is issued before the tile loads, because loads return in order and one issued later
+// would make its consumer wait for the tiles.  pos_lane: position id of token slot (lane & 7) of this wave
+// (used when group >= 4); slot: this lane's slot.  The rotation table sits in stage NS-1, which no tile load
+// targets before the first barrier of the tile loop.
+template <int D, int NW, int NS>
+__device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
+                                         const Walk& w, const RowCtx& rc, int group, int pos_lane, int slot,
+                                         const double* theta_rev, float sl2e, LDS_AS char* smem, bf16x8 (&qf)[D / 16])
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5;
+    double th = theta_rev[lane % (D / 2)];
+    u32x4 raw[D / 16];
+    load_q_raw<D>(q, rc, h, raw);
+    asm volatile("" : "+v"(th));
+    __builtin_amdgcn_sched_barrier(0);
+    issue_prologue<D, NW, NS>(k, v, w, smem, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    if (group >= 4) {
+        LDS_AS char* tab = smem + (NS - 1) * Geo<D>::STAGE_BYTES + wave * (ROT_SLOTS * 4 * D);
+        build_rot_table<D>(tab, th, lane, pos_lane);
+        rotate_q_shared<D>(raw, tab, slot, h, rc.valid, sl2e, qf);
+        __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the table reads are done before the stage is reused
+    } else {
+        rotate_q_direct<D>(raw, rc.pos, theta_rev, h, rc.valid, sl2e, qf);
     }
 }
 
@@ -376,17 +483,23 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     rc.orow = (sd.q_row0 + tok_local) * a.n_q_heads + kvh * g + rl % g;
     rc.key_lo = sd.kv_row0;
     rc.key_hi = sd.kv_row0 + n_doc + tok_local;
-    rc.pos = rc.valid ? (double)a.q_pos[sd.q_row0 + tok_local] : 0.0;
+    // position ids: per token slot of the wave when the rotation table is shared, else per row
+    const int wave_tok0 = tile * tpt + (32 * wave) / g;
+    int pos_lane = 0;
+    rc.pos = 0.0;
+    if (g >= 4) pos_lane = a.q_pos[sd.q_row0 + min(wave_tok0 + (lane & (ROT_SLOTS - 1)), sd.n_q - 1)];
+    else if (rc.valid) rc.pos = (double)a.q_pos[sd.q_row0 + tok_local];
+    const int slot = min(rl / g - (32 * wave) / g, ROT_SLOTS - 1);
 
     const int first_tok = tile * tpt;
     const int last_tok = min(first_tok + tpt, sd.n_q) - 1;
     const int sb = sd.kv_row0 + split * sd.split_len;
     const int se = min(sb + sd.split_len, sd.kv_row0 + sd.kv_len);
-    const int kt_begin = sb;
-    const int kt_end = min(se, sd.kv_row0 + n_doc + last_tok + 1);
+    const Walk w = make_walk(sb, min(se, sd.kv_row0 + n_doc + last_tok + 1), sd.kv_row0 + sd.kv_len - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, a.scale_log2e, qf);
+    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, g, pos_lane, slot, a.theta_rev,
+                        a.scale_log2e, smem, qf);
 
     Acc<D> acc;
 #pragma unroll
@@ -396,8 +509,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     acc.mref = 0.0f;
     acc.l = 0.0f;
 
-    attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, kt_begin, kt_end,
-                          sd.kv_row0 + sd.kv_len - 1, sd.kv_row0 + n_doc + first_tok, sd.kv_row0, smem, acc);
+    attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, w, rc, qf, sd.kv_row0 + n_doc + first_tok, sd.kv_row0, smem, acc);
 
     const float l_tot = acc.l + __shfl_xor(acc.l, 32);
     __builtin_amdgcn_s_barrier(); // all waves are done with the K/V stages; reuse them as store staging
@@ -507,7 +619,7 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     const int T = a.total_tokens;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 31, h = lane >> 5;
+    const int c = lane & 31;
     const int rl = 32 * wave + c;
     const int t = tile * tpt + rl / g;
     RowCtx rc;
@@ -516,14 +628,20 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     rc.key_lo = rc.valid ? a.tok_start[t] : 0;
     rc.key_hi = t;
     rc.pos = (double)(t - rc.key_lo);
+    // chunk-local position of token slot (lane & 7) of this wave
+    const int t_slot = min(tile * tpt + (32 * wave) / g + (lane & (ROT_SLOTS - 1)), T - 1);
+    const int pos_lane = t_slot - a.tok_start[t_slot];
+    const int slot = min(rl / g - (32 * wave) / g, ROT_SLOTS - 1);
 
     const int t_first = tile * tpt;
     const int t_last = min(t_first + tpt, T) - 1;
     const int lo_first = a.tok_start[t_first];
     const int lo_last = a.tok_start[t_last];
+    const Walk w = make_walk(lo_first, t_last + 1, T - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    load_q_frags<D>((const __bf16*)a.q, rc, a.theta_rev, h, a.scale_log2e, qf);
+    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, g, pos_lane, slot, a.theta_rev,
+                        a.scale_log2e, smem, qf);
 
     Acc<D> acc;
 #pragma unroll
@@ -533,8 +651,7 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     acc.mref = 0.0f;
     acc.l = 0.0f;
 
-    attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, a.n_kv_heads, kvh, rc, qf, lo_first, t_last + 1, T - 1,
-                          t_first, lo_last, smem, acc);
+    attn_tiles<D, NW, NS>((const __bf16*)a.k, (const __bf16*)a.v, w, rc, qf, t_first, lo_last, smem, acc);
 
     const float l_tot = acc.l + __shfl_xor(acc.l, 32);
     __builtin_amdgcn_s_barrier();
