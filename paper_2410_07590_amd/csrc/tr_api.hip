@@ -126,6 +126,7 @@ int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* o
     span = ((span + 255) / 256) * 256;
     if (span < 256) span = 256;
     if (span > 4096) span = 4096;
+    if (const char* e = getenv("TR_ASM_SPAN")) { if (atoi(e) >= 256) span = (atoi(e) / 256) * 256; } // tuning aid
 
     TrAssembleArgs a;
     memset(&a, 0, sizeof a);
@@ -310,7 +311,7 @@ namespace {
 struct ReqGeom { int32_t q_row0, n_q; int64_t kv_row0, kv_len; };
 
 constexpr int KEY_TILE = 64;
-constexpr int TARGET_ITEMS = 512;   // workgroup slots to fill: two 4-wave workgroups per CU on 256 CUs
+constexpr int TARGET_ITEMS = 256;   // workgroups to aim for when splitting keys: one per CU (more splits cost more partial traffic than they gain)
 constexpr int MIN_SPLIT_KEYS = 256;
 constexpr int MAX_SPLIT = 32;       // the combine kernel holds one split per lane of a half-wave
 
@@ -339,7 +340,7 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
     for (size_t r = r0; r < r1; ++r) max_rows = std::max<int64_t>(max_rows, (int64_t)reqs[r].n_q * g);
     const int wg_rows = pick_wg_rows(sh, max_rows);
     const int tpt = wg_rows / g;
-    const int target = env_int("TR_TARGET_ITEMS", wg_rows == 256 ? TARGET_ITEMS / 2 : TARGET_ITEMS);
+    const int target = env_int("TR_TARGET_ITEMS", TARGET_ITEMS);
     const int min_split_keys = env_int("TR_MIN_SPLIT_KEYS", MIN_SPLIT_KEYS);
     int64_t base_items = 0;
     for (size_t r = r0; r < r1; ++r) base_items += (int64_t)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads;
@@ -393,7 +394,7 @@ size_t prefix_ws_bytes(const tr_shape* sh, const std::vector<ReqGeom>& reqs)
     for (size_t r0 = 0; r0 < reqs.size(); r0 += TR_MAX_SEQ) {
         size_t r1 = r0 + TR_MAX_SEQ < reqs.size() ? r0 + TR_MAX_SEQ : reqs.size();
         int64_t rows = plan_prefix(sh, reqs, r0, r1, nullptr, nullptr, nullptr, nullptr);
-        size_t b = tr_align256((size_t)rows * sh->head_dim * 4) + tr_align256((size_t)rows * 8);
+        size_t b = tr_align256((size_t)rows * sh->head_dim * 2) + tr_align256((size_t)rows * 8);
         if (b > need) need = b;
     }
     return need;
@@ -423,8 +424,8 @@ int run_prefix(const tr_shape* sh, const void* q, const void* k, const void* v, 
         bool any_split = false;
         int toks = 0, wg_rows = 128;
         int64_t rows = plan_prefix(sh, reqs, r0, r1, &a, &any_split, &toks, &wg_rows);
-        a.ws_o = (float*)ws;
-        a.ws_ml = (float*)((char*)ws + tr_align256((size_t)rows * sh->head_dim * 4));
+        a.ws_o = (_Float16*)ws;
+        a.ws_ml = (float*)((char*)ws + tr_align256((size_t)rows * sh->head_dim * 2));
         if (a.n_seq == 0) continue;
         int rc = sh->dtype == TR_F32 ? tr_launch_prefix_attn_f32(a, sh->head_dim, toks * sh->n_q_heads, stream)
                                      : tr_launch_prefix_attn(a, sh->head_dim, wg_rows, any_split, toks * sh->n_q_heads, stream);
@@ -531,7 +532,7 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
     for (int m = 0; m < 64; ++m) a.theta_rev[m] = a.theta[m] / 6.283185307179586476925;
     rc = tr_launch_rope_table(table, max_chunk_len, shape->head_dim / 2, a.theta, s);
     if (rc) return rc;
-    rc = tr_launch_rope_rows(k, k_rot_out, cu_chunk_lens, n_chunks, tok_start, table, max_chunk_len, total_tokens, shape, s);
+    rc = tr_launch_rope_rows(k, k_rot_out, cu_chunk_lens, n_chunks, max_chunk_len, tok_start, table, max_chunk_len, total_tokens, shape, s);
     if (rc) return rc;
     a.q = q;
     a.k = k_rot_out;

@@ -31,6 +31,8 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_AS __attribute__((address_space(3)))
 #define GLB_AS __attribute__((address_space(1)))
@@ -411,14 +413,16 @@ __device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __b
 
 // Write the wave's 32 x D accumulator as rows: stage O^T through LDS (64 channels at a time) so that every
 // global store instruction writes whole contiguous row segments.
-//   PARTIAL = false: out[orow][:] = bf16(O / l)          PARTIAL = true: ws_o[prow][:] = O (fp32, unnormalised)
+//   PARTIAL = false: out[orow][:] = bf16(O / l)          PARTIAL = true: ws_o[prow][:] = fp16(O / l)
+// A partial is normalised by its own denominator, so it is a convex combination of V rows and fp16 (11 bits,
+// 8 times finer than the bf16 result) holds it; the merge weighs it with l again.
 template <int D, bool PARTIAL>
 __device__ __forceinline__ void store_rows(const Acc<D>& acc, float l_tot, bool valid, int64_t dst_row, void* dst,
                                            LDS_AS char* wave_buf, int lane)
 {
     constexpr int STRIDE = 64 * 4 + 16; // bytes per staged row: 64 floats + pad
     const int c = lane & 31, h = lane >> 5;
-    const float inv = PARTIAL ? 1.0f : 1.0f / l_tot;
+    const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     const int r_in = lane >> 4, c4 = lane & 15;
 #pragma unroll
     for (int half = 0; half < D / 64; ++half) {
@@ -441,7 +445,10 @@ __device__ __forceinline__ void store_rows(const Acc<D>& acc, float l_tot, bool 
             const int ok = __shfl((int)valid, row);
             if (ok) {
                 if (PARTIAL) {
-                    *(f32x4*)((float*)dst + drow * D + 64 * half + 4 * c4) = x;
+                    f16x4 y;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] = (_Float16)x[e];
+                    *(f16x4*)((_Float16*)dst + drow * D + 64 * half + 4 * c4) = y;
                 } else {
                     bf16x4 y;
 #pragma unroll
@@ -525,7 +532,8 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     }
 }
 
-// Merge the split-KV partial results: out = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).
+// Merge the split-KV partial results: out = sum_s w_s l_s P_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s) and
+// P_s = O_s / l_s the normalised partial of split s.
 // 32 lanes per output row (4 channels each); lane i of the row also owns split i's statistics.
 template <int D>
 __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int total_rows)
@@ -560,14 +568,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
     float M = m_i;
 #pragma unroll
     for (int o = 16; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-    const float w_i = (m_i == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_i - M);
-    float L = w_i * l_i;
+    const float w_i = (m_i == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_i - M) * l_i;
+    float L = w_i;
 #pragma unroll
     for (int o = 16; o >= 1; o >>= 1) L += __shfl_xor(L, o);
     float acc[CPLN];
 #pragma unroll
     for (int e = 0; e < CPLN; ++e) acc[e] = 0.0f;
-    const float* base = a.ws_o + prow0 * D + CPLN * lane_r;
+    const _Float16* base = a.ws_o + prow0 * D + CPLN * lane_r;
     const int row_lane0 = threadIdx.x & 32; // first lane of this row's half-wave
     // four splits per round so that four loads are in flight (the loop count is a run-time value)
     for (int sp0 = 0; sp0 < sd.n_split; sp0 += 4) {
@@ -577,12 +585,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
         for (int u = 0; u < 4; ++u) {
             const int sp = sp0 + u;
             const bool ok = sp < sd.n_split;
-            const float* p = base + (int64_t)(ok ? sp : 0) * pstride * D;
+            const _Float16* p = base + (int64_t)(ok ? sp : 0) * pstride * D;
             if (CPLN == 4) {
-                x[u] = *(const f32x4*)p;
+                const f16x4 t = *(const f16x4*)p;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[u][e] = (float)t[e];
             } else {
-                const float2 t = *(const float2*)p;
-                x[u][0] = t.x; x[u][1] = t.y; x[u][2] = 0.0f; x[u][3] = 0.0f;
+                const f16x2 t = *(const f16x2*)p;
+                x[u][0] = (float)t[0]; x[u][1] = (float)t[1]; x[u][2] = 0.0f; x[u][3] = 0.0f;
             }
             const float ws = __shfl(w_i, row_lane0 + (ok ? sp : 0));
             w[u] = ok ? ws : 0.0f;
@@ -606,6 +616,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
 }
 
 // ---- step 2 (offline): block-diagonal causal attention over packed chunks --------------------------------------
+// First row of the chunk that owns token t.  Clamped into [0, t] so that a cu_chunk_lens array that does not cover
+// every token can only give wrong numbers, never an access outside the tensors.
+__device__ __forceinline__ int chunk_start(const int32_t* tok_start, int t) { return min(max(tok_start[t], 0), t); }
+
 template <int D, int NW, int NS>
 __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBlockDiagArgs a)
 {
@@ -625,18 +639,18 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     RowCtx rc;
     rc.valid = (rl < tpt * g) && (t < T);
     rc.orow = t * a.n_q_heads + kvh * g + rl % g;
-    rc.key_lo = rc.valid ? a.tok_start[t] : 0;
+    rc.key_lo = rc.valid ? chunk_start(a.tok_start, t) : 0;
     rc.key_hi = t;
     rc.pos = (double)(t - rc.key_lo);
     // chunk-local position of token slot (lane & 7) of this wave
     const int t_slot = min(tile * tpt + (32 * wave) / g + (lane & (ROT_SLOTS - 1)), T - 1);
-    const int pos_lane = t_slot - a.tok_start[t_slot];
+    const int pos_lane = t_slot - chunk_start(a.tok_start, t_slot);
     const int slot = min(rl / g - (32 * wave) / g, ROT_SLOTS - 1);
 
     const int t_first = tile * tpt;
     const int t_last = min(t_first + tpt, T) - 1;
-    const int lo_first = a.tok_start[t_first];
-    const int lo_last = a.tok_start[t_last];
+    const int lo_first = chunk_start(a.tok_start, t_first);
+    const int lo_last = chunk_start(a.tok_start, t_last);
     const Walk w = make_walk(lo_first, t_last + 1, T - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];

@@ -2,6 +2,7 @@
 // and the offline key rotation.  All key rotations are computed in fp64 and rounded once to the
 // storage type, so the rotated keys are reproducible to the last bit against an fp64 definition.
 #include "tr_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -80,6 +81,17 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p)
 // the (cos, sin) of "its" pairs for this chunk's offset are loop constants.
 constexpr int ASM_UNROLL = 4;
 
+__device__ __forceinline__ void st_stream(uint4* p, uint4 x)
+{
+#ifdef TR_ASM_NT_STORE
+    u32x4 r;
+    r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
+    __builtin_nontemporal_store(r, (u32x4*)p);
+#else
+    *p = x;
+#endif
+}
+
 template <int DTYPE>
 __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
 {
@@ -97,6 +109,20 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
     if (u1 > run_units) u1 = run_units;
     const int tid = threadIdx.x;
 
+    const uint4* ks = (const uint4*)a.k_src + (int64_t)d.src_row * a.row_units;
+    const uint4* vs = (const uint4*)a.v_src + (int64_t)d.src_row * a.row_units;
+    uint4* kd = (uint4*)a.k_dst + (int64_t)d.dst_row * a.row_units;
+    uint4* vd = (uint4*)a.v_dst + (int64_t)d.dst_row * a.row_units;
+
+    // the first round of loads goes out before the angle work, which needs no data
+    uint4 kx[ASM_UNROLL], vx[ASM_UNROLL];
+    int64_t u = u0 + tid;
+#pragma unroll
+    for (int i = 0; i < ASM_UNROLL; ++i) {
+        const int64_t uu = u + 256 * i;
+        if (uu < u1) { kx[i] = ld_stream(ks + uu); vx[i] = ld_stream(vs + uu); }
+    }
+
     constexpr int P = Unit<DTYPE>::PAIRS;
     double c[P], s[P];
     const bool rot = d.delta != 0;
@@ -113,34 +139,33 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
         for (int p = 0; p < P; ++p) { c[p] = cs[m0 + p][0]; s[p] = cs[m0 + p][1]; }
     }
 
-    const uint4* ks = (const uint4*)a.k_src + (int64_t)d.src_row * a.row_units;
-    const uint4* vs = (const uint4*)a.v_src + (int64_t)d.src_row * a.row_units;
-    uint4* kd = (uint4*)a.k_dst + (int64_t)d.dst_row * a.row_units;
-    uint4* vd = (uint4*)a.v_dst + (int64_t)d.dst_row * a.row_units;
-
-    for (int64_t u = u0 + tid; u < u1; u += 256 * ASM_UNROLL) {
-        uint4 kx[ASM_UNROLL], vx[ASM_UNROLL];
+    while (u < u1) {
 #pragma unroll
         for (int i = 0; i < ASM_UNROLL; ++i) {
-            int64_t uu = u + 256 * i;
-            if (uu < u1) { kx[i] = ld_stream(ks + uu); vx[i] = ld_stream(vs + uu); }
-        }
-#pragma unroll
-        for (int i = 0; i < ASM_UNROLL; ++i) {
-            int64_t uu = u + 256 * i;
+            const int64_t uu = u + 256 * i;
             if (uu < u1) {
-                kd[uu] = rot ? Unit<DTYPE>::rotate(kx[i], c, s) : kx[i];
-                vd[uu] = vx[i];
+                st_stream(kd + uu, rot ? Unit<DTYPE>::rotate(kx[i], c, s) : kx[i]);
+                st_stream(vd + uu, vx[i]);
             }
+        }
+        u += 256 * ASM_UNROLL;
+#pragma unroll
+        for (int i = 0; i < ASM_UNROLL; ++i) {
+            const int64_t uu = u + 256 * i;
+            if (uu < u1) { kx[i] = ld_stream(ks + uu); vx[i] = ld_stream(vs + uu); }
         }
     }
 }
 
 // ---- query append: cache rows of the query tokens (K' rotated at q_pos, V copied) -------------------------
-// One thread per (token, pair m): its angle is shared by all KV heads of the token.
+// One thread per (token, pair m): its angle is shared by all KV heads of the token (the fp64 sincos is by far
+// the longest thing a thread does, so it is done once per thread), and the loads go out before it.
+constexpr int APPEND_MAX_HEADS = 16; // KV heads held in registers at once; more go round the loop again
+
 template <int DTYPE>
 __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
 {
+    typedef typename std::conditional<DTYPE == TR_BF16, uint32_t, float2>::type Pair; // one (even, odd) channel pair
     const int half = a.head_dim >> 1;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int tok = (int)(gid / half), m = (int)(gid % half);
@@ -151,24 +176,34 @@ __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
     const int i = tok - base;
     const int64_t src_row = (int64_t)a.desc[r].q_row0 + i;
     const int64_t dst_row = (int64_t)a.desc[r].dst_row0 + i;
-    double sn, cn;
-    sincos((double)a.q_pos[src_row] * a.theta[m], &sn, &cn);
-    for (int h = 0; h < a.n_kv_heads; ++h) {
-        const int64_t so = (src_row * a.n_kv_heads + h) * a.head_dim + 2 * m;
-        const int64_t dn = (dst_row * a.n_kv_heads + h) * a.head_dim + 2 * m;
-        if (DTYPE == TR_BF16) {
-            uint32_t w = *(const uint32_t*)((const uint16_t*)a.k_new + so);
-            double ya, yb;
-            rotate_pair(bf16_bits_to_double(w & 0xffffu), bf16_bits_to_double(w >> 16), cn, sn, ya, yb);
-            *(uint32_t*)((uint16_t*)a.cache_k + dn) = double_to_bf16_bits(ya) | (double_to_bf16_bits(yb) << 16);
-            *(uint32_t*)((uint16_t*)a.cache_v + dn) = *(const uint32_t*)((const uint16_t*)a.v_new + so);
-        } else {
-            float2 w = *(const float2*)((const float*)a.k_new + so);
-            double ya, yb;
-            rotate_pair((double)w.x, (double)w.y, cn, sn, ya, yb);
-            *(float2*)((float*)a.cache_k + dn) = make_float2(__double2float_rn(ya), __double2float_rn(yb));
-            *(float2*)((float*)a.cache_v + dn) = *(const float2*)((const float*)a.v_new + so);
-        }
+    const Pair* ks = (const Pair*)a.k_new + src_row * a.n_kv_heads * half + m;
+    const Pair* vs = (const Pair*)a.v_new + src_row * a.n_kv_heads * half + m;
+    Pair* kd = (Pair*)a.cache_k + dst_row * a.n_kv_heads * half + m;
+    Pair* vd = (Pair*)a.cache_v + dst_row * a.n_kv_heads * half + m;
+    const double angle = (double)a.q_pos[src_row] * a.theta[m];
+    double sn = 0.0, cn = 1.0;
+    for (int h0 = 0; h0 < a.n_kv_heads; h0 += APPEND_MAX_HEADS) {
+        Pair kx[APPEND_MAX_HEADS], vx[APPEND_MAX_HEADS];
+#pragma unroll
+        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
+            if (h0 + j < a.n_kv_heads) { kx[j] = ks[(h0 + j) * half]; vx[j] = vs[(h0 + j) * half]; }
+        if (h0 == 0) sincos(angle, &sn, &cn);
+#pragma unroll
+        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
+            if (h0 + j < a.n_kv_heads) {
+                double xa, xb, ya, yb;
+                if constexpr (DTYPE == TR_BF16) {
+                    xa = bf16_bits_to_double(kx[j] & 0xffffu);
+                    xb = bf16_bits_to_double(kx[j] >> 16);
+                } else {
+                    xa = (double)kx[j].x;
+                    xb = (double)kx[j].y;
+                }
+                rotate_pair(xa, xb, cn, sn, ya, yb);
+                if constexpr (DTYPE == TR_BF16) kd[(h0 + j) * half] = double_to_bf16_bits(ya) | (double_to_bf16_bits(yb) << 16);
+                else kd[(h0 + j) * half] = make_float2(__double2float_rn(ya), __double2float_rn(yb));
+                vd[(h0 + j) * half] = vx[j];
+            }
     }
 }
 
@@ -186,37 +221,48 @@ __global__ __launch_bounds__(256) void rope_table_kernel(double2* table, int n_p
     table[gid] = make_double2(cn, sn);
 }
 
-// One thread per 16-byte unit of a key row.  Also records, per token, the first row of its chunk.
+// Grid (row blocks, chunks); a thread owns one 16-byte unit position inside a head for one token and walks the
+// KV heads, so the (cos, sin) it fetched from the table serve every head.  Row blocks stride over the chunk, so
+// every token of [cu[c], cu[c+1]) is covered whatever the chunk's length.  Also records, per token, the first
+// row of its chunk.
+constexpr int ROPE_ROWS_HEADS = 8; // KV heads in flight per thread
+
 template <int DTYPE>
-__global__ __launch_bounds__(256) void rope_rows_kernel(const uint4* k, uint4* k_rot, const int32_t* cu, int n_chunks,
-                                                        int32_t* tok_start, const double2* table, int table_rows,
-                                                        int64_t total_tokens, int row_units, int head_units, int half_dim)
+__global__ __launch_bounds__(256) void rope_rows_kernel(const uint4* k, uint4* k_rot, const int32_t* cu, int32_t* tok_start,
+                                                        const double2* table, int table_rows, int64_t total_tokens,
+                                                        int n_kv_heads, int head_units, int half_dim)
 {
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (gid >= total_tokens * row_units) return;
-    const int t = (int)(gid / row_units);
-    const int unit = (int)(gid % row_units);
-    // chunk that owns token t: largest c with cu[c] <= t
-    int lo = 0, hi = n_chunks - 1;
-    while (lo < hi) {
-        int mid = (lo + hi + 1) >> 1;
-        if (cu[mid] <= t) lo = mid; else hi = mid - 1;
-    }
-    const int start = cu[lo];
-    if (unit == 0) tok_start[t] = start;
-    int pos = t - start;
-    if (pos > table_rows - 1) pos = table_rows - 1; // caller promised max_chunk_len; never read past the table
     constexpr int P = Unit<DTYPE>::PAIRS;
-    const int m0 = (unit % head_units) * P;
-    double c[P], s[P];
+    const int chunk = blockIdx.y;
+    int start = cu[chunk], end = cu[chunk + 1];
+    if (start < 0) start = 0;
+    if (end > total_tokens) end = (int)total_tokens;
+    const int tpb = 256 / head_units; // tokens per block
+    const int unit = threadIdx.x % head_units;
+    const int row_units = n_kv_heads * head_units;
+    for (int t = start + blockIdx.x * tpb + threadIdx.x / head_units; t < end; t += gridDim.x * tpb) {
+        if (unit == 0) tok_start[t] = start;
+        int pos = t - start;
+        if (pos > table_rows - 1) pos = table_rows - 1; // caller promised max_chunk_len; never read past the table
+        const uint4* src = k + (int64_t)t * row_units + unit;
+        uint4* dst = k_rot + (int64_t)t * row_units + unit;
+        for (int h0 = 0; h0 < n_kv_heads; h0 += ROPE_ROWS_HEADS) {
+            uint4 x[ROPE_ROWS_HEADS];
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        double2 e = table[(int64_t)pos * half_dim + m0 + p];
-        c[p] = e.x;
-        s[p] = e.y;
+            for (int j = 0; j < ROPE_ROWS_HEADS; ++j)
+                if (h0 + j < n_kv_heads) x[j] = ld_stream(src + (h0 + j) * head_units);
+            double c[P], s[P];
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const double2 e = table[(int64_t)pos * half_dim + unit * P + p];
+                c[p] = e.x;
+                s[p] = e.y;
+            }
+#pragma unroll
+            for (int j = 0; j < ROPE_ROWS_HEADS; ++j)
+                if (h0 + j < n_kv_heads) dst[(h0 + j) * head_units] = (pos == 0) ? x[j] : Unit<DTYPE>::rotate(x[j], c, s);
+        }
     }
-    uint4 x = k[gid];
-    k_rot[gid] = (pos == 0) ? x : Unit<DTYPE>::rotate(x, c, s);
 }
 
 } // namespace
@@ -253,21 +299,27 @@ int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* t
     return TR_OK;
 }
 
-int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int32_t* tok_start,
+int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int max_chunk_len, int32_t* tok_start,
                         const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s)
 {
     const int eb = tr_elem_bytes(shape);
-    const int row_units = shape->n_kv_heads * shape->head_dim * eb / 16;
     const int head_units = shape->head_dim * eb / 16;
-    int64_t threads = total_tokens * row_units;
-    if (threads <= 0) return TR_OK;
-    dim3 grid((unsigned)((threads + 255) / 256));
-    if (shape->dtype == TR_BF16)
-        hipLaunchKernelGGL(rope_rows_kernel<TR_BF16>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu, n_chunks,
-                           tok_start, (const double2*)table, table_rows, total_tokens, row_units, head_units, shape->head_dim / 2);
-    else
-        hipLaunchKernelGGL(rope_rows_kernel<TR_F32>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu, n_chunks,
-                           tok_start, (const double2*)table, table_rows, total_tokens, row_units, head_units, shape->head_dim / 2);
-    TR_HIP(hipGetLastError());
+    if (total_tokens <= 0 || n_chunks <= 0) return TR_OK;
+    const int tpb = 256 / head_units;
+    int row_blocks = (max_chunk_len + tpb - 1) / tpb;
+    if (row_blocks < 1) row_blocks = 1;
+    if (row_blocks > 1024) row_blocks = 1024;
+    // grid.y carries the chunk index: at most 65535 chunks per launch
+    for (int c0 = 0; c0 < n_chunks; c0 += 65535) {
+        const int nc = n_chunks - c0 < 65535 ? n_chunks - c0 : 65535;
+        dim3 grid((unsigned)row_blocks, (unsigned)nc);
+        if (shape->dtype == TR_BF16)
+            hipLaunchKernelGGL(rope_rows_kernel<TR_BF16>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu + c0, tok_start,
+                               (const double2*)table, table_rows, total_tokens, shape->n_kv_heads, head_units, shape->head_dim / 2);
+        else
+            hipLaunchKernelGGL(rope_rows_kernel<TR_F32>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu + c0, tok_start,
+                               (const double2*)table, table_rows, total_tokens, shape->n_kv_heads, head_units, shape->head_dim / 2);
+        TR_HIP(hipGetLastError());
+    }
     return TR_OK;
 }

@@ -98,7 +98,7 @@ struct TrPrefixArgs {
     const void* v;
     const int32_t* q_pos;
     void* out;
-    float* ws_o;  // [partial rows][head_dim] unnormalised outputs
+    _Float16* ws_o; // [partial rows][head_dim] partial outputs, each normalised by its own denominator
     float* ws_ml; // [partial rows][2] reference maximum (log2 domain) and softmax denominator
     int32_t n_seq;
     int32_t n_items;
@@ -137,7 +137,7 @@ int tr_launch_append(const TrAppendArgs& a, int dtype, hipStream_t s);
 int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool any_split, int total_rows, hipStream_t s);
 int tr_launch_prefix_attn_f32(const TrPrefixArgs& a, int head_dim, int total_rows, hipStream_t s);
 int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* theta, hipStream_t s);
-int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int32_t* tok_start,
+int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int max_chunk_len, int32_t* tok_start,
                         const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s);
 int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s);
 int tr_launch_blockdiag_attn_f32(const TrBlockDiagArgs& a, int head_dim, hipStream_t s);
