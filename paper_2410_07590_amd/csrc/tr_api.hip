@@ -543,7 +543,10 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
     a.n_q_heads = shape->n_q_heads;
     a.n_kv_heads = shape->n_kv_heads;
     a.group = shape->n_q_heads / shape->n_kv_heads;
-    const int wg_rows = pick_wg_rows(shape, (int64_t)max_chunk_len * a.group);
+    // chunks are short (a row tile walks a few key tiles only), so two independent 4-wave workgroups per CU, which
+    // overlap one's prologue and epilogue with the other's tile loop, beat one 8-wave workgroup
+    const int forced_rows = env_int("TR_WG_ROWS", 0);
+    const int wg_rows = forced_rows == 256 ? 256 : 128;
     a.tok_per_tile = wg_rows / a.group;
     a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);
     a.scale = (float)(1.0 / sqrt((double)shape->head_dim));

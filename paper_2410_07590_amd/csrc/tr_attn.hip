@@ -208,13 +208,12 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const _
     }
 }
 
-// One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// One 64-key tile in two phases.  Phase A: S^T = K Q^T and the online softmax, leaving P^T packed as bf16 B operands.
+// Phase B: O^T += V^T P^T.
 template <int D>
-__device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf16x8 (&qf)[D / 16], const RowCtx& rc, int kt,
-                                             bool need_mask, const int (&koff)[D / 16], const int (&voff)[D / 32], int h,
-                                             Acc<D>& acc)
+__device__ __forceinline__ void scores_softmax(LDS_AS const char* stage, const bf16x8 (&qf)[D / 16], const RowCtx& rc, int kt,
+                                               bool need_mask, const int (&koff)[D / 16], int h, Acc<D>& acc, bf16x8 (&bpk)[2][2])
 {
-    using G = Geo<D>;
     // scores relative to the row reference, in the log2 domain (the queries carry log2(e)/sqrt(d)): the
     // accumulators start at -mref, so P = exp2(S) needs no further arithmetic
     f32x16 s[2];
@@ -264,7 +263,6 @@ __device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf1
             for (int e = 0; e < 16; ++e) s[kb][e] -= delta;
     }
     // P = exp2(S), packed to bf16 B-operands; the denominator sums the rounded weights the product uses
-    bf16x8 bpk[2][2];
     {
         bf16x2 ones;
         ones[0] = (__bf16)1.0f;
@@ -283,7 +281,14 @@ __device__ __forceinline__ void compute_tile(LDS_AS const char* stage, const bf1
             }
         acc.l = l;
     }
-    // O^T += V^T P^T.  k-slot j of k-step (kb, t) is key 32 kb + 16 t + 8 (j >> 2) + 4 h + (j & 3).
+}
+
+// O^T += V^T P^T.  k-slot j of k-step (kb, t) is key 32 kb + 16 t + 8 (j >> 2) + 4 h + (j & 3).
+template <int D>
+__device__ __forceinline__ void weighted_values(LDS_AS const char* stage, const bf16x8 (&bpk)[2][2], const int (&voff)[D / 32],
+                                                Acc<D>& acc)
+{
+    using G = Geo<D>;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -363,6 +368,7 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
     }
 
     const int n_tiles = w.n_tiles;
+    bf16x8 bpk[2][2];
     for (int t = 0; t < n_tiles; ++t) {
         const int kt = w.kt_begin + t * KT;
         // tile t has landed once at most the loads of the tiles issued after it are outstanding
@@ -378,7 +384,8 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
         if (active) {
             LDS_AS const char* stage = smem + (t % NS) * G::STAGE_BYTES;
             const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
-            compute_tile<D>(stage, qf, rc, kt, need_mask, koff, voff, h, acc);
+            scores_softmax<D>(stage, qf, rc, kt, need_mask, koff, h, acc, bpk);
+            weighted_values<D>(stage, bpk, voff, acc);
         }
     }
 }
