@@ -147,6 +147,18 @@ int tr_prefill_attn_batched(const tr_shape* shape, const void* q, const void* k,
                             const int64_t* cache_row_start /*host*/, int32_t n_req, void* out,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- decode step over the assembled cache (Sec. 3.4 step 7: answer generation reuses the cache) -----------
+ * One new token per request, for a batch of requests: q, out: device [n_req, n_q_heads, head_dim]; q_pos:
+ * device [n_req]; request r's cache is rows [cache_row_start[r], cache_row_start[r+1]) of k/v (host array),
+ * and its LAST row is the new token itself (append it first with tr_kv_append[_batched]); the token attends
+ * every row of its range.  Same arithmetic as tr_prefill_attn with n_q = 1; the kernel behind it lets the
+ * waves of a workgroup split the keys instead of the rows, because the g rows of a KV head cannot fill a
+ * workgroup.  An empty range is an error (TR_ERR_INVALID_ARG).  Workspace as for tr_prefill_attn. */
+size_t tr_decode_attn_workspace_size(const tr_shape* shape, const int64_t* cache_row_start /*host*/, int32_t n_req);
+int tr_decode_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* q_pos /*device*/,
+                   const int64_t* cache_row_start /*host [n_req+1]*/, int32_t n_req, void* out,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- offline document prefill, attention part (Sec. 3.4 step 2; independent attention, Sec. 3.2) ----------
  * Chunks packed on one token axis: q device [total_tokens, n_q_heads, d], k, v device
  * [total_tokens, n_kv_heads, d], all RAW; cu_chunk_lens: DEVICE int32 [n_chunks+1], cu[0] = 0,

@@ -24,6 +24,7 @@ EXPORTS = [
     "tr_kv_assemble", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched",
     "tr_prefill_attn_workspace_size", "tr_prefill_attn",
     "tr_prefill_attn_batched_workspace_size", "tr_prefill_attn_batched",
+    "tr_decode_attn_workspace_size", "tr_decode_attn",
     "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
 ]
 
@@ -56,7 +57,7 @@ def lib():
         L = C.CDLL(_build.LIB)
         L.tr_last_error.restype = C.c_char_p
         for name in ("tr_prefill_attn_workspace_size", "tr_prefill_attn_batched_workspace_size",
-                     "tr_chunk_prefill_attn_workspace_size"):
+                     "tr_decode_attn_workspace_size", "tr_chunk_prefill_attn_workspace_size"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -188,6 +189,18 @@ def tr_prefill_attn_batched(shape, q, k, v, q_pos, cu_q, cache_row_start, out, w
     _check(lib().tr_prefill_attn_batched(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), cu_p, rs_p,
                                          C.c_int32(cu.size - 1), _dev(out), _dev(workspace), C.c_size_t(ws_bytes),
                                          _stream(stream)))
+
+
+def tr_decode_attn_workspace_size(shape, cache_row_start):
+    rs, rs_p = _host(cache_row_start, np.int64)
+    return int(lib().tr_decode_attn_workspace_size(C.byref(shape), rs_p, C.c_int32(rs.size - 1)))
+
+
+def tr_decode_attn(shape, q, k, v, q_pos, cache_row_start, out, workspace=None, stream=None):
+    rs, rs_p = _host(cache_row_start, np.int64)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().tr_decode_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), rs_p, C.c_int32(rs.size - 1),
+                                _dev(out), _dev(workspace), C.c_size_t(ws_bytes), _stream(stream)))
 
 
 def tr_chunk_prefill_attn_workspace_size(shape, total_tokens, max_chunk_len):

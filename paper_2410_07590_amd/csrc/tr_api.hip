@@ -326,8 +326,9 @@ int env_int(const char* name, int dflt)
 int pick_wg_rows(const tr_shape* sh, int64_t max_rows_per_kv_head)
 {
     const int forced = env_int("TR_WG_ROWS", 0);
-    if (forced == 128 || forced == 256) return forced;
-    (void)sh;
+    const int g = sh->n_q_heads / sh->n_kv_heads;
+    if (forced == 128 || forced == 256 || (forced == 32 && g <= 32)) return forced;
+    if (max_rows_per_kv_head <= 32) return 32; // decode and other very short queries: waves split keys, not rows
     return max_rows_per_kv_head >= 512 ? 256 : 128;
 }
 
@@ -357,8 +358,9 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
         const int64_t max_split = (q.kv_len + min_split_keys - 1) / min_split_keys;
         if (n_split > max_split) n_split = (int)max_split;
         if (n_split < 1) n_split = 1;
+        const int key_tile = wg_rows == 32 ? 2 * KEY_TILE : KEY_TILE; // the short-query kernel walks 128 keys a step
         int64_t split_len = (q.kv_len + n_split - 1) / n_split;
-        split_len = ((split_len + KEY_TILE - 1) / KEY_TILE) * KEY_TILE;
+        split_len = ((split_len + key_tile - 1) / key_tile) * key_tile;
         n_split = (int)((q.kv_len + split_len - 1) / split_len);
         if (a) {
             TrSeqDesc& d = a->seq[n];
@@ -495,6 +497,35 @@ extern "C" int tr_prefill_attn_batched(const tr_shape* shape, const void* q, con
     if (n_req == 0 || cu_q[n_req] == 0) return TR_OK;
     if (!q || !k || !v || !q_pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn_batched: NULL pointer");
     return run_prefix(shape, q, k, v, q_pos, reqs, out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+// ---- decode step: one query token per request ---------------------------------------------------------------------
+namespace {
+int decode_cu(int32_t n_req, std::vector<int32_t>* cu)
+{
+    if (n_req < 0) return tr_fail(TR_ERR_INVALID_ARG, "n_req < 0");
+    cu->resize((size_t)n_req + 1);
+    for (int32_t r = 0; r <= n_req; ++r) (*cu)[r] = r;
+    return TR_OK;
+}
+} // namespace
+
+extern "C" size_t tr_decode_attn_workspace_size(const tr_shape* shape, const int64_t* cache_row_start, int32_t n_req)
+{
+    std::vector<int32_t> cu;
+    if (decode_cu(n_req, &cu)) return 0;
+    return tr_prefill_attn_batched_workspace_size(shape, cu.data(), cache_row_start, n_req);
+}
+
+extern "C" int tr_decode_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* q_pos,
+                              const int64_t* cache_row_start, int32_t n_req, void* out, void* workspace,
+                              size_t workspace_bytes, void* stream)
+{
+    tr_clear_error();
+    std::vector<int32_t> cu;
+    int rc = decode_cu(n_req, &cu);
+    if (rc) return rc;
+    return tr_prefill_attn_batched(shape, q, k, v, q_pos, cu.data(), cache_row_start, n_req, out, workspace, workspace_bytes, stream);
 }
 
 // ---- offline chunk prefill --------------------------------------------------------------------------------------------

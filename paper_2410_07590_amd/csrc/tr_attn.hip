@@ -186,15 +186,17 @@ template <int D> struct Acc {
     float l;          // this half-wave's share of the softmax denominator
 };
 
-// Issue this wave's share of the direct global->LDS loads of tile [kt, kt+64) into one stage.
-template <int D, int NW>
+// Issue this wave's share of the direct global->LDS loads of tile [kt, kt+KROWS) into one stage (K rows, then V rows).
+template <int D, int NW, int KROWS = KT>
 __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const __bf16* __restrict__ v, int64_t row_elems,
                                            int head_off, int kt, int key_clamp, LDS_AS char* stage, int wave, int lane)
 {
     using G = Geo<D>;
+    constexpr int NI = KROWS / G::RPI;
+    static_assert(NI % NW == 0, "tile loads must divide evenly over the waves");
     const int r_in = lane / G::CPR, pc = lane % G::CPR;
 #pragma unroll
-    for (int ii = 0; ii < G::NI / NW; ++ii) {
+    for (int ii = 0; ii < NI / NW; ++ii) {
         const int i = wave + NW * ii;
         const int row = i * G::RPI + r_in;
         int key = kt + row;
@@ -204,34 +206,35 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const _
         const int64_t base = (int64_t)key * row_elems + head_off;
         __builtin_amdgcn_global_load_lds((const GLB_AS void*)(k + base + ck * 8), (LDS_AS void*)(stage + i * 1024), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((const GLB_AS void*)(v + base + cv * 8),
-                                         (LDS_AS void*)(stage + G::TILE_BYTES + i * 1024), 16, 0, 0);
+                                         (LDS_AS void*)(stage + KROWS * D * 2 + i * 1024), 16, 0, 0);
     }
 }
 
-// One 64-key tile in two phases.  Phase A: S^T = K Q^T and the online softmax, leaving P^T packed as bf16 B operands.
-// Phase B: O^T += V^T P^T.
-template <int D>
-__device__ __forceinline__ void scores_softmax(LDS_AS const char* stage, const bf16x8 (&qf)[D / 16], const RowCtx& rc, int kt,
-                                               bool need_mask, const int (&koff)[D / 16], int h, Acc<D>& acc, bf16x8 (&bpk)[2][2])
+// One tile of 32 KB keys in two phases.  Phase A: S^T = K Q^T and the online softmax, leaving P^T packed as bf16 B
+// operands.  Phase B: O^T += V^T P^T.  krows / vrows point at the tile's first K / V row in LDS, kt is its first key.
+template <int D, int KB>
+__device__ __forceinline__ void scores_softmax(LDS_AS const char* krows, const bf16x8 (&qf)[D / 16], const RowCtx& rc, int kt,
+                                               bool need_mask, const int (&koff)[D / 16], int h, Acc<D>& acc, bf16x8 (&bpk)[KB][2])
 {
     // scores relative to the row reference, in the log2 domain (the queries carry log2(e)/sqrt(d)): the
     // accumulators start at -mref, so P = exp2(S) needs no further arithmetic
-    f32x16 s[2];
+    f32x16 s[KB];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[kb][e] = -acc.mref;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 a0 = *(LDS_AS const bf16x8*)(stage + koff[ks]);
-        const bf16x8 a1 = *(LDS_AS const bf16x8*)(stage + koff[ks] + 32 * D * 2);
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s[1], 0, 0, 0);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const bf16x8 a = *(LDS_AS const bf16x8*)(krows + koff[ks] + kb * 32 * D * 2);
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+        }
     }
     // accumulator element e of block kb is key kt + 32 kb + 8 (e >> 2) + 4 h + (e & 3), query column c
     if (need_mask) { // workgroup-uniform: only tiles that straddle a mask edge
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int key = kt + 32 * kb + 8 * (e >> 2) + 4 * h + (e & 3);
@@ -240,7 +243,7 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* stage, const b
     }
     float mx = -INFINITY;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32)); // both half-waves hold keys of the same query column
@@ -258,7 +261,7 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* stage, const b
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc.o[db][e] *= alpha;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) s[kb][e] -= delta;
     }
@@ -269,7 +272,7 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* stage, const b
         ones[1] = (__bf16)1.0f;
         float l = acc.l;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 bf16x2 pr;
@@ -284,20 +287,19 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* stage, const b
 }
 
 // O^T += V^T P^T.  k-slot j of k-step (kb, t) is key 32 kb + 16 t + 8 (j >> 2) + 4 h + (j & 3).
-template <int D>
-__device__ __forceinline__ void weighted_values(LDS_AS const char* stage, const bf16x8 (&bpk)[2][2], const int (&voff)[D / 32],
+template <int D, int KB>
+__device__ __forceinline__ void weighted_values(LDS_AS const char* vrows, const bf16x8 (&bpk)[KB][2], const int (&voff)[D / 32],
                                                 Acc<D>& acc)
 {
-    using G = Geo<D>;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const bf16x8 bp = bpk[kb][t];
-            const int rbase = G::TILE_BYTES + (32 * kb + 16 * t) * D * 2;
+            const int rbase = (32 * kb + 16 * t) * D * 2;
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                LDS_AS const char* p0 = stage + rbase + voff[db];
+                LDS_AS const char* p0 = vrows + rbase + voff[db];
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 8 * D * 2));
                 const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -384,8 +386,8 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
         if (active) {
             LDS_AS const char* stage = smem + (t % NS) * G::STAGE_BYTES;
             const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
-            scores_softmax<D>(stage, qf, rc, kt, need_mask, koff, h, acc, bpk);
-            weighted_values<D>(stage, bpk, voff, acc);
+            scores_softmax<D, 2>(stage, qf, rc, kt, need_mask, koff, h, acc, bpk);
+            weighted_values<D, 2>(stage + G::TILE_BYTES, bpk, voff, acc);
         }
     }
 }
@@ -536,6 +538,198 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
         store_rows<D, true>(acc, l_tot, rc.valid, prow, a.ws_o, wave_buf, lane);
         // a split in which the row saw no key reports m = -inf so that the merge ignores it
         if (rc.valid && h == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(l_tot > 0.0f ? acc.mref : -INFINITY, l_tot);
+    }
+}
+
+// ---- step 6 / step 7 for very short queries (decode: one new token per request) --------------------------------
+// When the packed rows of a (request, KV head) fit one 32-row MFMA block, giving each wave its own rows would
+// leave three of four waves idle.  Here all four waves hold the SAME rows and split the keys instead: a tile is
+// 128 keys, wave w owns keys [32 w, 32 w + 32) of it, and the four partial results are merged through LDS at
+// the end.  The kernel then streams K/V at four times the rate of one wave, which is what a memory-bound
+// decode step needs.
+constexpr int SHORT_NW = 4, SHORT_NS = 2, SHORT_KT = 32 * SHORT_NW;
+
+template <int D> constexpr int short_stage_bytes() { return 2 * SHORT_KT * D * 2; }
+template <int D> constexpr int short_merge_row_bytes() { return D * 4 + 16; }
+
+template <int D>
+__global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPrefixArgs a)
+{
+    using G = Geo<D>;
+    constexpr int NW = SHORT_NW, NS = SHORT_NS;
+    constexpr int STAGE = short_stage_bytes<D>();
+    extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+    LDS_AS char* smem = (LDS_AS char*)smem_raw;
+    const int item = xcd_remap(blockIdx.x, a.n_items);
+    int lo = 0, hi = a.n_seq - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (a.seq[mid].item0 <= item) lo = mid; else hi = mid - 1;
+    }
+    const TrSeqDesc sd = a.seq[lo];
+    const int local = item - sd.item0;
+    const int tile = local % sd.n_tiles;
+    const int rest = local / sd.n_tiles;
+    const int split = rest % sd.n_split;
+    const int kvh = rest / sd.n_split;
+    const int g = a.group, tpt = a.tok_per_tile;
+    const int n_doc = sd.kv_len - sd.n_q;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int i16 = lane & 15, colhalf = (lane >> 4) & 1;
+    const int tok_local = tile * tpt + c / g;
+    RowCtx rc;
+    rc.valid = (c < tpt * g) && (tok_local < sd.n_q);
+    rc.orow = (sd.q_row0 + tok_local) * a.n_q_heads + kvh * g + c % g;
+    rc.key_lo = sd.kv_row0;
+    rc.key_hi = sd.kv_row0 + n_doc + tok_local;
+    int pos_lane = 0;
+    rc.pos = 0.0;
+    if (g >= 4) pos_lane = a.q_pos[sd.q_row0 + min(tile * tpt + (lane & (ROT_SLOTS - 1)), sd.n_q - 1)];
+    else if (rc.valid) rc.pos = (double)a.q_pos[sd.q_row0 + tok_local];
+    const int slot = min(c / g, ROT_SLOTS - 1);
+
+    const int first_tok = tile * tpt;
+    const int last_tok = min(first_tok + tpt, sd.n_q) - 1;
+    const int sb = sd.kv_row0 + split * sd.split_len;
+    const int se = min(sb + sd.split_len, sd.kv_row0 + sd.kv_len);
+    const int kt_begin = sb;
+    const int kt_end = min(se, sd.kv_row0 + n_doc + last_tok + 1);
+    const int n_tiles = kt_end > kt_begin ? (kt_end - kt_begin + SHORT_KT - 1) / SHORT_KT : 0;
+    const int key_clamp = sd.kv_row0 + sd.kv_len - 1;
+    const int64_t row_elems = (int64_t)a.n_kv_heads * D;
+    const int head_off = kvh * D;
+    const __bf16* kp = (const __bf16*)a.k;
+    const __bf16* vp = (const __bf16*)a.v;
+
+    // prologue: ordinary loads, then tile 0, then the rotation (every wave rotates the same rows)
+    double th = a.theta_rev[lane % (D / 2)];
+    u32x4 raw[D / 16];
+    load_q_raw<D>((const __bf16*)a.q, rc, h, raw);
+    asm volatile("" : "+v"(th));
+    __builtin_amdgcn_sched_barrier(0);
+    if (n_tiles > 0) issue_tile<D, NW, SHORT_KT>(kp, vp, row_elems, head_off, kt_begin, key_clamp, smem, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 qf[D / 16];
+    if (g >= 4) {
+        LDS_AS char* tab = smem + STAGE + wave * (ROT_SLOTS * 4 * D); // stage 1 is free until the first barrier
+        build_rot_table<D>(tab, th, lane, pos_lane);
+        rotate_q_shared<D>(raw, tab, slot, h, rc.valid, a.scale_log2e, qf);
+        __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0)
+    } else {
+        rotate_q_direct<D>(raw, rc.pos, a.theta_rev, h, rc.valid, a.scale_log2e, qf);
+    }
+
+    Acc<D> acc;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc.o[db][e] = 0.0f;
+    acc.mref = 0.0f;
+    acc.l = 0.0f;
+
+    const int wave_hi_max = wave_max_i(rc.valid ? rc.key_hi : INT32_MIN);
+    const int mask_hi_min = sd.kv_row0 + n_doc + first_tok;
+    int koff[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) koff[ks] = (32 * wave + c) * D * 2 + (((2 * ks + h) ^ G::kswz(c)) * 16);
+    int voff[D / 32];
+    {
+        const int r = 4 * h + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+            voff[db] = (32 * wave + r) * D * 2 + (4 * (db ^ G::vswz(r)) + 2 * colhalf + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
+    }
+
+    bf16x8 bpk[1][2];
+    for (int t = 0; t < n_tiles; ++t) {
+        const int kt = kt_begin + t * SHORT_KT;
+        wait_vm<0>(); // two stages: tile t is the only load in flight here
+        __builtin_amdgcn_s_barrier(); // tile t is in LDS; everyone is done with tile t-1
+        if (t + 1 < n_tiles)
+            issue_tile<D, NW, SHORT_KT>(kp, vp, row_elems, head_off, kt + SHORT_KT, key_clamp, smem + ((t + 1) % NS) * STAGE, wave, lane);
+        const int ktw = kt + 32 * wave; // this wave's 32 keys
+        if (ktw <= wave_hi_max && ktw < kt_end) {
+            LDS_AS const char* stage = smem + (t % NS) * STAGE;
+            const bool need_mask = ktw + 31 > mask_hi_min;
+            scores_softmax<D, 1>(stage, qf, rc, ktw, need_mask, koff, h, acc, bpk);
+            weighted_values<D, 1>(stage + SHORT_KT * D * 2, bpk, voff, acc);
+        }
+    }
+
+    // merge the four key slices: every wave parks (m, l) and its unnormalised O in LDS
+    constexpr int ROWB = short_merge_row_bytes<D>();
+    const float l_tot = acc.l + __shfl_xor(acc.l, 32);
+    __builtin_amdgcn_s_barrier(); // all waves are done with the K/V stages
+    LDS_AS char* obuf = smem + wave * (32 * ROWB);
+    LDS_AS float* mlbuf = (LDS_AS float*)(smem + NW * 32 * ROWB);
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            f32x4 x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = acc.o[db][4 * q4 + e];
+            *(LDS_AS f32x4*)(obuf + c * ROWB + (32 * db + 8 * q4 + 4 * h) * 4) = x;
+        }
+    if (h == 0) {
+        mlbuf[(wave * 32 + c) * 2] = l_tot > 0.0f ? acc.mref : -INFINITY;
+        mlbuf[(wave * 32 + c) * 2 + 1] = l_tot;
+    }
+    __syncthreads();
+    // thread -> (row r, D/8 consecutive channels)
+    constexpr int CPT = D / 8;
+    const int r = tid >> 3, j = tid & 7;
+    float mw[NW], lw[NW], M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        mw[w] = mlbuf[(w * 32 + r) * 2];
+        lw[w] = mlbuf[(w * 32 + r) * 2 + 1];
+        M = fmaxf(M, mw[w]);
+    }
+    float L = 0.0f, ww[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        ww[w] = (mw[w] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw[w] - M);
+        L += ww[w] * lw[w];
+    }
+    float o[CPT];
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) o[e] = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+#pragma unroll
+        for (int e4 = 0; e4 < CPT / 4; ++e4) {
+            const f32x4 x = *(LDS_AS const f32x4*)(smem + w * (32 * ROWB) + r * ROWB + (CPT * j + 4 * e4) * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[4 * e4 + e] += ww[w] * x[e];
+        }
+    const int r_tok = tile * tpt + r / g;
+    const bool r_valid = (r < tpt * g) && (r_tok < sd.n_q);
+    if (!r_valid) return;
+    const float inv = L > 0.0f ? 1.0f / L : 0.0f;
+    if (sd.n_split == 1) {
+        __bf16* op = (__bf16*)a.out + ((int64_t)(sd.q_row0 + r_tok) * a.n_q_heads + kvh * g + r % g) * D + CPT * j;
+#pragma unroll
+        for (int e4 = 0; e4 < CPT / 4; ++e4) {
+            bf16x4 y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = (__bf16)(o[4 * e4 + e] * inv);
+            *(bf16x4*)(op + 4 * e4) = y;
+        }
+    } else {
+        const int rows_s = sd.n_q * g;
+        const int64_t prow = (int64_t)sd.ws_row0 + (int64_t)(split * a.n_kv_heads + kvh) * rows_s + r_tok * g + r % g;
+        _Float16* op = a.ws_o + prow * D + CPT * j;
+#pragma unroll
+        for (int e4 = 0; e4 < CPT / 4; ++e4) {
+            f16x4 y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = (_Float16)(o[4 * e4 + e] * inv);
+            *(f16x4*)(op + 4 * e4) = y;
+        }
+        if (j == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(L > 0.0f ? M : -INFINITY, L);
     }
 }
 
@@ -702,6 +896,23 @@ int launch_prefix(const TrPrefixArgs& a, hipStream_t s)
     return TR_OK;
 }
 
+template <int D>
+int launch_short(const TrPrefixArgs& a, hipStream_t s)
+{
+    auto kern = short_attn_kernel<D>;
+    constexpr int ring = SHORT_NS * short_stage_bytes<D>();
+    constexpr int merge = SHORT_NW * 32 * short_merge_row_bytes<D>() + SHORT_NW * 32 * 8;
+    constexpr int lds = ring > merge ? ring : merge;
+    static bool configured = false;
+    if (!configured) {
+        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.n_items), dim3(64 * SHORT_NW), lds, s, a);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
+}
+
 template <int D, int NW, int NS>
 int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
 {
@@ -719,12 +930,14 @@ int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
 
 } // namespace
 
-// wg_rows: 128 (4 waves, 2-stage ring, two workgroups per CU) or 256 (8 waves, 4-stage ring, one per CU)
+// wg_rows: 128 (4 waves, 2-stage ring, two workgroups per CU), 256 (8 waves, 4-stage ring, one per CU) or 32 (the
+// short-query kernel: 4 waves share 32 rows and split the keys)
 int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool any_split, int total_rows, hipStream_t s)
 {
     if (a.n_items <= 0) return TR_OK;
     int rc;
-    if (head_dim == 128) rc = wg_rows == 256 ? launch_prefix<128, 8, 4>(a, s) : launch_prefix<128, 4, 2>(a, s);
+    if (wg_rows == 32) rc = head_dim == 128 ? launch_short<128>(a, s) : launch_short<64>(a, s);
+    else if (head_dim == 128) rc = wg_rows == 256 ? launch_prefix<128, 8, 4>(a, s) : launch_prefix<128, 4, 2>(a, s);
     else rc = wg_rows == 256 ? launch_prefix<64, 8, 4>(a, s) : launch_prefix<64, 4, 2>(a, s);
     if (rc) return rc;
     if (any_split) {

@@ -109,7 +109,7 @@ def test_config4_full_sampled_rows(B):
 
 
 # ---- configuration 3: batched serving, mixed modes ---------------------------------------------------------------
-def _run_batched(B, cfg, store, sd, reqs):
+def _run_batched(B, cfg, store, sd, reqs, decode=False):
     sh = cfg.shape
     gs = sd.shape
     n_req = len(reqs)
@@ -130,15 +130,20 @@ def _run_batched(B, cfg, store, sd, reqs):
     out = torch.full(q.shape, float("nan"), dtype=dt, device="cuda")
     B.tr_kv_assemble_batched(sd, ids, cu_chunks, modes, cache_row_start, cache_k, cache_v)
     B.tr_kv_append_batched(gs, k_q, v_q, q_pos, cu_q, cache_row_start, cache_k, cache_v)
-    ws = B.workspace(B.tr_prefill_attn_batched_workspace_size(gs, cu_q, cache_row_start))
-    B.tr_prefill_attn_batched(gs, q, cache_k, cache_v, q_pos, cu_q, cache_row_start, out, ws)
+    if decode:   # one token per request: the decode entry point (same arithmetic, cu_q implied)
+        assert all(r.n_q == 1 for r in reqs)
+        ws = B.workspace(B.tr_decode_attn_workspace_size(gs, cache_row_start))
+        B.tr_decode_attn(gs, q, cache_k, cache_v, q_pos, cache_row_start, out, ws)
+    else:
+        ws = B.workspace(B.tr_prefill_attn_batched_workspace_size(gs, cu_q, cache_row_start))
+        B.tr_prefill_attn_batched(gs, q, cache_k, cache_v, q_pos, cu_q, cache_row_start, out, ws)
     torch.cuda.synchronize()
     return cache_k.cpu(), cache_v.cpu(), out.cpu(), cache_row_start, cu_q
 
 
-def _check_batched(B, cfg, store, sd, reqs, rows_per_req=None):
+def _check_batched(B, cfg, store, sd, reqs, rows_per_req=None, decode=False):
     sh = cfg.shape
-    ck, cv, out, crs, cu_q = _run_batched(B, cfg, store, sd, reqs)
+    ck, cv, out, crs, cu_q = _run_batched(B, cfg, store, sd, reqs, decode)
     worst = 0.0
     for r, req in enumerate(reqs):
         rows = None
@@ -174,6 +179,56 @@ def test_config3_full_batched(B):
     sd = _store_dev(B, cfg.shape, store)
     reqs = synth.make_requests(cfg, store)
     print("config3: max abs err %.3e (4 sampled query tokens per request)" % _check_batched(B, cfg, store, sd, reqs, rows_per_req=4))
+
+
+# ---- decode step (Sec. 3.4 step 7): one new token per request over its assembled cache ---------------------------
+DECODE_SHAPES = [synth.QWEN2_7B, synth.LLAMA3_8B, synth.Shape(14, 2, 64, "bf16", 1.0e6), synth.Shape(8, 8, 64, "bf16", 1.0e4),
+                 synth.Shape(32, 1, 128, "bf16", 5.0e5)]
+
+
+@pytest.mark.parametrize("shape_no", range(len(DECODE_SHAPES)))
+def test_decode_batch_ragged(B, shape_no):
+    """Ragged cache lengths from 1 chunk row up to a few hundred rows, both position schemes, group sizes 7, 4, 1 and 32."""
+    sh = DECODE_SHAPES[shape_no]
+    cfg = synth.scaled(synth.CONFIGS[3], shape=sh, store_chunks=30, chunk_len_lo=1, chunk_len_hi=130, n_requests=9,
+                       chunks_per_request=3, n_q_lo=1, n_q_hi=1)
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, sh, store)
+    reqs = synth.make_requests(cfg, store)
+    print("decode ragged %s: max abs err %.3e" % (sh, _check_batched(B, cfg, store, sd, reqs, decode=True)))
+
+
+def test_decode_split_keys(B):
+    """Few requests with long caches: the key range is split over workgroups and merged by the combine kernel."""
+    cfg = synth.scaled(synth.CONFIGS[3], store_chunks=12, chunk_len_lo=300, chunk_len_hi=700, n_requests=3,
+                       chunks_per_request=5, n_q_lo=1, n_q_hi=1)
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    reqs = synth.make_requests(cfg, store)
+    gs = H.gpu_shape(B, cfg.shape)
+    crs = np.concatenate([[0], np.cumsum([r.n_doc + 1 for r in reqs])]).astype(np.int64)
+    assert B.tr_decode_attn_workspace_size(gs, crs) > 0          # this case does split
+    print("decode split: max abs err %.3e" % _check_batched(B, cfg, store, sd, reqs, decode=True))
+
+
+def test_decode_full_batch64_kv4k(B):
+    """64 requests x 8 chunks of 512 rows at the Qwen2-7B shape: the size the decode bench line is quoted on."""
+    cfg = synth.scaled(synth.CONFIGS[2], n_requests=64, n_q_lo=1, n_q_hi=1)
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    reqs = synth.make_requests(cfg, store)
+    print("decode 64 x 4097: max abs err %.3e" % _check_batched(B, cfg, store, sd, reqs, decode=True))
+
+
+def test_short_query_kernel_with_causal_rows(B, monkeypatch):
+    """The key-splitting kernel forced onto queries of up to 40 tokens: several row tiles, causal mask among them."""
+    monkeypatch.setenv("TR_WG_ROWS", "32")
+    cfg = synth.scaled(synth.CONFIGS[3], store_chunks=40, chunk_len_lo=20, chunk_len_hi=90, n_requests=5,
+                       chunks_per_request=3, n_q_lo=3, n_q_hi=40)
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    reqs = synth.make_requests(cfg, store)
+    print("short-query kernel, n_q up to 40: max abs err %.3e" % _check_batched(B, cfg, store, sd, reqs))
 
 
 # ---- configuration 5: offline chunk prefill ------------------------------------------------------------------------
