@@ -115,6 +115,15 @@ int tr_kv_append(const tr_shape* shape, const void* k_new, const void* v_new, co
                  int32_t n_q, void* cache_k, void* cache_v, int64_t dst_row, int64_t cache_capacity_rows,
                  void* stream);
 
+/* Assemble and append of ONE request in a single launch (Sec. 3.4 step 5 followed by the query tokens' own rows):
+ * exactly tr_kv_assemble(store, chunk_ids, offsets, n_chunks, pos_mode, out_k, out_v, ...) followed by
+ * tr_kv_append(shape, k_new, v_new, q_pos, n_q, out_k, out_v, dst_row = offsets[n_chunks], ...), same results bit
+ * for bit, one kernel instead of two.  out_capacity_rows must hold n_doc + n_q rows.  Same errors as those two. */
+int tr_kv_assemble_append(const tr_store* store, const int32_t* chunk_ids /*host*/, const int64_t* offsets /*host*/,
+                          int32_t n_chunks, int32_t pos_mode, const void* k_new, const void* v_new,
+                          const int32_t* q_pos /*device*/, int32_t n_q, void* out_k, void* out_v,
+                          int64_t out_capacity_rows, void* stream);
+
 /* Batched form: tokens packed [cu_q[n_req], ...]; request r's n_q_r tokens go to the LAST n_q_r rows of its
  * cache range [cache_row_start[r], cache_row_start[r+1]). */
 int tr_kv_append_batched(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos /*device*/,

@@ -21,7 +21,7 @@ TR_ROPE_INTERLEAVED, TR_ROPE_HALF = 0, 1
 
 EXPORTS = [
     "tr_last_error", "tr_store_create", "tr_store_destroy", "tr_plan",
-    "tr_kv_assemble", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched",
+    "tr_kv_assemble", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched", "tr_kv_assemble_append",
     "tr_prefill_attn_workspace_size", "tr_prefill_attn",
     "tr_prefill_attn_batched_workspace_size", "tr_prefill_attn_batched",
     "tr_decode_attn_workspace_size", "tr_decode_attn",
@@ -156,6 +156,14 @@ def tr_kv_append(shape, k_new, v_new, q_pos, cache_k, cache_v, dst_row, stream=N
     _check(lib().tr_kv_append(C.byref(shape), _dev(k_new), _dev(v_new), _dev(q_pos), C.c_int32(k_new.shape[0]),
                               _dev(cache_k), _dev(cache_v), C.c_int64(dst_row), C.c_int64(cache_k.shape[0]),
                               _stream(stream)))
+
+
+def tr_kv_assemble_append(store, chunk_ids, offsets, pos_mode, k_new, v_new, q_pos, out_k, out_v, stream=None):
+    ids, ids_p = _host(chunk_ids, np.int32)
+    off, off_p = _host(offsets, np.int64)
+    _check(lib().tr_kv_assemble_append(store.handle, ids_p, off_p, C.c_int32(ids.size), C.c_int32(pos_mode), _dev(k_new), _dev(v_new),
+                                       _dev(q_pos), C.c_int32(k_new.shape[0]), _dev(out_k), _dev(out_v), C.c_int64(out_k.shape[0]),
+                                       _stream(stream)))
 
 
 def tr_kv_append_batched(shape, k_new, v_new, q_pos, cu_q, cache_row_start, cache_k, cache_v, stream=None):

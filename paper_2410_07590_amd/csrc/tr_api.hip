@@ -112,7 +112,9 @@ namespace {
 
 struct CopyRun { int64_t src_row, dst_row, n_rows, delta; };
 
-int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* out_k, void* out_v, hipStream_t stream)
+// tail (optional): query tokens appended by extra blocks of the last launch
+int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* out_k, void* out_v, hipStream_t stream,
+                const TrAppendTail* tail = nullptr)
 {
     const tr_shape* sh = &store->shape;
     const int eb = tr_elem_bytes(sh);
@@ -155,6 +157,11 @@ int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* o
         }
         a.n_desc = n;
         if (n == 0) continue;
+        if (tail && i == runs.size()) { // last launch carries the append
+            a.app = *tail;
+            a.app.first_block = blocks;
+            blocks += (int)(((int64_t)tail->n_q * (sh->head_dim / 2) + 255) / 256);
+        }
         int rc = tr_launch_assemble(a, sh->dtype, blocks, stream);
         if (rc) return rc;
     }
@@ -274,6 +281,52 @@ extern "C" int tr_kv_append(const tr_shape* shape, const void* k_new, const void
     d[0].n_q = n_q;
     d[0].dst_row0 = (int32_t)dst_row;
     return launch_append(shape, k_new, v_new, q_pos, d, cache_k, cache_v, (hipStream_t)stream);
+}
+
+// assemble + append of one request in a single launch
+extern "C" int tr_kv_assemble_append(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
+                                     int32_t pos_mode, const void* k_new, const void* v_new, const int32_t* q_pos, int32_t n_q,
+                                     void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
+{
+    tr_clear_error();
+    if (!store) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble_append: store is NULL");
+    if (n_q < 0 || n_chunks < 0) return tr_fail(TR_ERR_INVALID_ARG, "negative count");
+    if (n_chunks > 0 && !offsets) return tr_fail(TR_ERR_INVALID_ARG, "offsets is NULL");
+    const int64_t n_doc_claimed = n_chunks > 0 ? offsets[n_chunks] : 0;
+    // no documents or no query tokens: nothing to fuse
+    if (n_q == 0) return tr_kv_assemble(store, chunk_ids, offsets, n_chunks, pos_mode, out_k, out_v, out_capacity_rows, stream);
+    if (!k_new || !v_new || !q_pos || !out_k || !out_v) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble_append: NULL pointer");
+    if (n_chunks == 0 || n_doc_claimed == 0) { // validated by tr_kv_assemble below
+        int rc = tr_kv_assemble(store, chunk_ids, offsets, n_chunks, pos_mode, out_k, out_v, out_capacity_rows, stream);
+        if (rc) return rc;
+        return tr_kv_append(&store->shape, k_new, v_new, q_pos, n_q, out_k, out_v, 0, out_capacity_rows, stream);
+    }
+    if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
+    if (!chunk_ids) return tr_fail(TR_ERR_INVALID_ARG, "chunk_ids is NULL");
+    if (out_capacity_rows < 0 || out_capacity_rows > ROW_LIMIT) return tr_fail(TR_ERR_INVALID_ARG, "out_capacity_rows out of range");
+    const int n_store = (int)store->row_start.size() - 1;
+    std::vector<CopyRun> runs;
+    runs.reserve(n_chunks);
+    int64_t off = 0;
+    for (int i = 0; i < n_chunks; ++i) {
+        const int32_t c = chunk_ids[i];
+        if (c < 0 || c >= n_store) return tr_fail(TR_ERR_BAD_CHUNK_ID, "chunk_ids[%d] = %d outside [0, %d)", i, c, n_store);
+        if (offsets[i] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, the prefix sum of the chunk lengths is %lld", i, (long long)offsets[i], (long long)off);
+        const int64_t len = store->row_start[c + 1] - store->row_start[c];
+        if (len > 0) runs.push_back({store->row_start[c], off, len, pos_mode == TR_POS_REORDERED ? off : 0}); // the last run carries the tail
+        off += len;
+    }
+    if (offsets[n_chunks] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, expected n_doc = %lld", n_chunks, (long long)offsets[n_chunks], (long long)off);
+    if (off + n_q > out_capacity_rows) return tr_fail(TR_ERR_BAD_PLAN, "plan needs %lld rows, the cache holds %lld", (long long)(off + n_q), (long long)out_capacity_rows);
+    TrAppendTail tail;
+    tail.k_new = k_new;
+    tail.v_new = v_new;
+    tail.q_pos = q_pos;
+    tail.n_q = n_q;
+    tail.dst_row0 = (int32_t)off;
+    tail.first_block = 0;
+    tail.n_kv_heads = store->shape.n_kv_heads;
+    return launch_runs(store, runs, out_k, out_v, (hipStream_t)stream, &tail);
 }
 
 extern "C" int tr_kv_append_batched(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos,

@@ -75,6 +75,48 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p)
     return make_uint4(r[0], r[1], r[2], r[3]);
 }
 
+// ---- one (token, pair m) of the query append: K' rotated at q_pos, V copied, for every KV head ----------------
+// The angle is shared by all KV heads of the token (the fp64 sincos is by far the longest thing a thread does, so
+// it is done once per thread), and the loads go out before it.
+constexpr int APPEND_MAX_HEADS = 16; // KV heads held in registers at once; more go round the loop again
+
+template <int DTYPE>
+__device__ __forceinline__ void append_pair(const void* k_new, const void* v_new, const int32_t* q_pos, void* cache_k,
+                                            void* cache_v, int n_kv_heads, int half, double theta_m, int64_t src_row,
+                                            int64_t dst_row, int m)
+{
+    typedef typename std::conditional<DTYPE == TR_BF16, uint32_t, float2>::type Pair; // one (even, odd) channel pair
+    const Pair* ks = (const Pair*)k_new + src_row * n_kv_heads * half + m;
+    const Pair* vs = (const Pair*)v_new + src_row * n_kv_heads * half + m;
+    Pair* kd = (Pair*)cache_k + dst_row * n_kv_heads * half + m;
+    Pair* vd = (Pair*)cache_v + dst_row * n_kv_heads * half + m;
+    const double angle = (double)q_pos[src_row] * theta_m;
+    double sn = 0.0, cn = 1.0;
+    for (int h0 = 0; h0 < n_kv_heads; h0 += APPEND_MAX_HEADS) {
+        Pair kx[APPEND_MAX_HEADS], vx[APPEND_MAX_HEADS];
+#pragma unroll
+        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
+            if (h0 + j < n_kv_heads) { kx[j] = ks[(h0 + j) * half]; vx[j] = vs[(h0 + j) * half]; }
+        if (h0 == 0) sincos(angle, &sn, &cn);
+#pragma unroll
+        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
+            if (h0 + j < n_kv_heads) {
+                double xa, xb, ya, yb;
+                if constexpr (DTYPE == TR_BF16) {
+                    xa = bf16_bits_to_double(kx[j] & 0xffffu);
+                    xb = bf16_bits_to_double(kx[j] >> 16);
+                } else {
+                    xa = (double)kx[j].x;
+                    xb = (double)kx[j].y;
+                }
+                rotate_pair(xa, xb, cn, sn, ya, yb);
+                if constexpr (DTYPE == TR_BF16) kd[(h0 + j) * half] = double_to_bf16_bits(ya) | (double_to_bf16_bits(yb) << 16);
+                else kd[(h0 + j) * half] = make_float2(__double2float_rn(ya), __double2float_rn(yb));
+                vd[(h0 + j) * half] = vx[j];
+            }
+    }
+}
+
 // ---- KV-cache formation: Sec. 3.4 step 5 with the reordered-position rotation of Sec. 3.2 -------------------
 // A run of rows is contiguous in the store and in the cache, so a block moves a flat span of 16-byte
 // units.  A thread's unit index modulo the units-per-head never changes while it strides by 256, hence
@@ -97,6 +139,15 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
 {
     __shared__ double cs[64][2];
     const int b = blockIdx.x;
+    if (a.app.n_q > 0 && b >= a.app.first_block) {
+        // tail blocks: the request's own query tokens, one thread per (token, pair)
+        const int gid = (b - a.app.first_block) * 256 + (int)threadIdx.x;
+        const int tok = gid / a.half_dim, m = gid % a.half_dim;
+        if (tok < a.app.n_q)
+            append_pair<DTYPE>(a.app.k_new, a.app.v_new, a.app.q_pos, a.k_dst, a.v_dst, a.app.n_kv_heads, a.half_dim, a.theta[m],
+                               tok, (int64_t)a.app.dst_row0 + tok, m);
+        return;
+    }
     int lo = 0, hi = a.n_desc - 1;
     while (lo < hi) {
         int mid = (lo + hi + 1) >> 1;
@@ -158,14 +209,9 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
 }
 
 // ---- query append: cache rows of the query tokens (K' rotated at q_pos, V copied) -------------------------
-// One thread per (token, pair m): its angle is shared by all KV heads of the token (the fp64 sincos is by far
-// the longest thing a thread does, so it is done once per thread), and the loads go out before it.
-constexpr int APPEND_MAX_HEADS = 16; // KV heads held in registers at once; more go round the loop again
-
 template <int DTYPE>
 __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
 {
-    typedef typename std::conditional<DTYPE == TR_BF16, uint32_t, float2>::type Pair; // one (even, odd) channel pair
     const int half = a.head_dim >> 1;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int tok = (int)(gid / half), m = (int)(gid % half);
@@ -174,37 +220,8 @@ __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
     int r = 0, base = 0;
     while (r + 1 < a.n_desc && tok >= base + a.desc[r].n_q) { base += a.desc[r].n_q; ++r; }
     const int i = tok - base;
-    const int64_t src_row = (int64_t)a.desc[r].q_row0 + i;
-    const int64_t dst_row = (int64_t)a.desc[r].dst_row0 + i;
-    const Pair* ks = (const Pair*)a.k_new + src_row * a.n_kv_heads * half + m;
-    const Pair* vs = (const Pair*)a.v_new + src_row * a.n_kv_heads * half + m;
-    Pair* kd = (Pair*)a.cache_k + dst_row * a.n_kv_heads * half + m;
-    Pair* vd = (Pair*)a.cache_v + dst_row * a.n_kv_heads * half + m;
-    const double angle = (double)a.q_pos[src_row] * a.theta[m];
-    double sn = 0.0, cn = 1.0;
-    for (int h0 = 0; h0 < a.n_kv_heads; h0 += APPEND_MAX_HEADS) {
-        Pair kx[APPEND_MAX_HEADS], vx[APPEND_MAX_HEADS];
-#pragma unroll
-        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
-            if (h0 + j < a.n_kv_heads) { kx[j] = ks[(h0 + j) * half]; vx[j] = vs[(h0 + j) * half]; }
-        if (h0 == 0) sincos(angle, &sn, &cn);
-#pragma unroll
-        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
-            if (h0 + j < a.n_kv_heads) {
-                double xa, xb, ya, yb;
-                if constexpr (DTYPE == TR_BF16) {
-                    xa = bf16_bits_to_double(kx[j] & 0xffffu);
-                    xb = bf16_bits_to_double(kx[j] >> 16);
-                } else {
-                    xa = (double)kx[j].x;
-                    xb = (double)kx[j].y;
-                }
-                rotate_pair(xa, xb, cn, sn, ya, yb);
-                if constexpr (DTYPE == TR_BF16) kd[(h0 + j) * half] = double_to_bf16_bits(ya) | (double_to_bf16_bits(yb) << 16);
-                else kd[(h0 + j) * half] = make_float2(__double2float_rn(ya), __double2float_rn(yb));
-                vd[(h0 + j) * half] = vx[j];
-            }
-    }
+    append_pair<DTYPE>(a.k_new, a.v_new, a.q_pos, a.cache_k, a.cache_v, a.n_kv_heads, half, a.theta[m],
+                       (int64_t)a.desc[r].q_row0 + i, (int64_t)a.desc[r].dst_row0 + i, m);
 }
 
 // ---- offline key rotation (Sec. 3.4 step 2): K' = R(t - cu[c]) k -------------------------------------------

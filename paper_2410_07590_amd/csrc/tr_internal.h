@@ -42,6 +42,16 @@ struct TrCopyDesc {
     int32_t blk_start; // first block of the grid that works on this run
 };
 #define TR_MAX_COPY_DESC 128
+// optional tail of an assemble launch: one request's query tokens appended by the blocks from first_block on
+struct TrAppendTail {
+    const void* k_new;
+    const void* v_new;
+    const int32_t* q_pos;
+    int32_t n_q; // 0: no tail
+    int32_t dst_row0;
+    int32_t first_block;
+    int32_t n_kv_heads;
+};
 struct TrAssembleArgs {
     const void* k_src;
     const void* v_src;
@@ -54,6 +64,7 @@ struct TrAssembleArgs {
     int32_t half_dim;   // head_dim / 2
     int32_t pad_;
     double theta[64];
+    TrAppendTail app;
     TrCopyDesc desc[TR_MAX_COPY_DESC];
 };
 

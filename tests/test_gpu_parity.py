@@ -89,6 +89,40 @@ def test_no_documents_and_noops(B):
 
 
 # ---- configurations 2 and 4 at full size -----------------------------------------------------------------------
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+def test_assemble_append_in_one_launch_matches_the_two_calls(B, mode):
+    """tr_kv_assemble_append == tr_kv_assemble followed by tr_kv_append, byte for byte, including an empty last chunk,
+    no documents at all, and no query tokens."""
+    sh = synth.QWEN2_7B
+    cfg = synth.scaled(synth.CONFIGS[3], store_chunks=12, chunk_len_lo=0, chunk_len_hi=150, n_requests=4,
+                       chunks_per_request=4, n_q_lo=0, n_q_hi=70)
+    store = synth.make_store(cfg)
+    lens = np.diff(store.row_start)
+    sd = _store_dev(B, sh, store)
+    gs = sd.shape
+    reqs = synth.make_requests(cfg, store, pos_mode=mode)
+    empty = [int(c) for c in np.nonzero(lens == 0)[0]]
+    cases = [(r.chunk_ids, r) for r in reqs] + [(np.zeros(0, np.int32), reqs[0])]
+    if empty:
+        cases.append((np.concatenate([reqs[1].chunk_ids[:2], [empty[0]]]).astype(np.int32), reqs[1]))
+    for ids, r in cases:
+        offsets, _ = B.tr_plan(sd, ids, mode, want_pos_ids=False)
+        n_doc = int(offsets[-1])
+        rows = n_doc + r.n_q
+        q_pos = torch.from_numpy((n_doc + np.arange(r.n_q)).astype(np.int32)).cuda()
+        kq, vq = r.k_q.cuda(), r.v_q.cuda()
+        two_k = torch.full((rows + 3, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=sh.torch_dtype, device="cuda")
+        two_v, one_k, one_v = (torch.full_like(two_k, float("nan")) for _ in range(3))
+        B.tr_kv_assemble(sd, ids, offsets, mode, two_k, two_v)
+        if r.n_q:
+            B.tr_kv_append(gs, kq, vq, q_pos, two_k, two_v, n_doc)
+        B.tr_kv_assemble_append(sd, ids, offsets, mode, kq, vq, q_pos, one_k, one_v)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.bits(one_k.cpu()), H.bits(two_k.cpu()))   # NaN guard rows included: nothing written past the end
+        assert np.array_equal(H.bits(one_v.cpu()), H.bits(two_v.cpu()))
+        assert not torch.isnan(one_k[:rows].float()).any()
+
+
 def test_config2_full(B):
     cfg = synth.CONFIGS[2]
     store = synth.make_store(cfg)
