@@ -3,7 +3,8 @@
 
 A step is one pass of the online path for one request of configuration 2 (Qwen2-7B attention
 shape, 8 retrieved chunks x 512 tokens out of a 256-chunk store, 64 query tokens, reordered
-positions): gather plan -> tr_kv_assemble -> tr_kv_append -> tr_prefill_attn, one layer.
+positions): gather plan -> tr_kv_assemble_append (KV gather with RoPE re-rotation, and the query
+tokens' own rows, one launch) -> tr_prefill_attn, one layer.
 Steps cycle through 16 requests with different chunk ids and their own cache buffers, so the
 store is read from HBM rather than from a warm cache.  The K timed steps are captured once in a
 HIP graph (the way a serving loop would issue them) and replayed between two synchronisations;
@@ -14,6 +15,7 @@ other kernels at the sizes where they are bandwidth- or MFMA-bound (configuratio
 the CPU oracle timed on the host cores.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -28,11 +30,12 @@ N_VARIANTS = 16
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters read
 # on a copy kernel of known size (see profiles/ and the design doc).  None where not measured.
 MEASURED_TRAFFIC = {
-    ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 43267266,       # prefix_attn 26.0 MB (15.8 MB of split partials written) + combine 17.2 MB
-    ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16899349,
-    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268636206,
-    ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 208421815,  # prefix_attn 171.7 MB + combine 36.7 MB
-    ("tr_chunk_prefill_attn", "offline-64x512"): 808238715,    # table 0.6 MB + key rotation 135.3 MB + attention 672.3 MB
+    ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 23825433,       # prefix_attn 16.5 MB (6.2 MB of split partials written) + combine 7.3 MB
+    ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16954640,
+    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268660236,
+    ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174887734,  # prefix_attn 154.9 MB + combine 20.0 MB
+    ("tr_chunk_prefill_attn", "offline-64x512"): 808062056,    # table 0.6 MB + key rotation 135.2 MB + attention 672.3 MB
+    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537995462,
 }
 
 
@@ -74,7 +77,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time the eager loop instead of a HIP graph replay")
     ap.add_argument("--case", default=None,
                     help="profiling aid: run only one kernel path --iters times, eagerly, and print nothing but a note "
-                         "(step2, assemble2, attn2, assemble4, attn4, offline5, copy)")
+                         "(step2, assemble2, attn2, assemble4, attn4, offline5, decode2, copy)")
     ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -131,22 +134,29 @@ def main():
     def attn(v):
         B.tr_prefill_attn(gs, q, v["cache_k"], v["cache_v"], q_pos, v["kv_len"], v["out"], ws)
 
+    def assemble_append(v):
+        offsets, _ = B.tr_plan(sd, v["ids"], base_req.pos_mode, want_pos_ids=False)   # a1: plan (host)
+        B.tr_kv_assemble_append(sd, v["ids"], offsets, base_req.pos_mode, k_q, v_q, q_pos, v["cache_k"], v["cache_v"])
+
     def step(i):
         v = variants[i % N_VARIANTS]
-        assemble(v)
-        append(v)
+        assemble_append(v)
         attn(v)
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
 
-    # eager loop (host-driven)
+    # eager loop (host-driven).  Python's cyclic collector is paused for it: with torch loaded one full collection
+    # takes about 40 ms, a thousand steps' worth, and it would fire a few times inside the loop.
+    gc.collect()
+    gc.disable()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i)
     torch.cuda.synchronize()
     eager_s = time.perf_counter() - t0
+    gc.enable()
 
     if args.no_graph:
         total_s = eager_s
@@ -175,6 +185,7 @@ def main():
 
     t_asm = _time_calls(torch, cyc_call(assemble), it)
     t_app = _time_calls(torch, cyc_call(append), it)
+    t_asa = _time_calls(torch, cyc_call(assemble_append), it)
     t_att = _time_calls(torch, cyc_call(attn), it)
 
     kv_len = variants[0]["kv_len"]
@@ -198,18 +209,21 @@ def main():
 
     # dominant kernel of the step: query-prefill attention (prefix_attn_kernel + its split-KV combine)
     roofline = mfma_roof("tr_prefill_attn", cfg.name, att_flops, t_att, att_bytes)
-    roof_extra = [hbm_roof("tr_kv_assemble", cfg.name, asm_bytes, t_asm),
+    asa_bytes = asm_bytes + acct.append_bytes(n_q, sh.n_kv_heads, sh.head_dim, eb)
+    roof_extra = [hbm_roof("tr_kv_assemble_append", cfg.name, asa_bytes, t_asa),
+                  hbm_roof("tr_kv_assemble", cfg.name, asm_bytes, t_asm),
                   {"kernel": "tr_kv_append", "workload": cfg.name, "avg_us": round(t_app[0], 2), "median_us": round(t_app[1], 2)}]
 
     result = {
-        "metric": "us/layer query-prefill over assembled KV (plan + assemble + append + prefill attention)",
+        "metric": "us/layer query-prefill over assembled KV (plan + assemble and append + prefill attention)",
         "value": round(us_per_step, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(us_per_step / 1e3, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config 2: %s (28 q heads, 4 kv heads, head_dim 128, 8 of 256 chunks x 512 tokens, 64 query tokens, reordered positions)" % cfg.name,
                    "timed_as": "eager" if args.no_graph else "hip_graph_replay", "request_variants": N_VARIANTS},
         "eager_us_per_step": round(eager_s / args.steps * 1e6, 3),
-        "kernel_us": {"assemble": round(t_asm[0], 2), "append": round(t_app[0], 2), "prefill_attn": round(t_att[0], 2)},
+        "kernel_us": {"assemble_append": round(t_asa[0], 2), "prefill_attn": round(t_att[0], 2),
+                      "assemble_alone": round(t_asm[0], 2), "append_alone": round(t_app[0], 2)},
         "roofline": roofline,
     }
 
@@ -217,6 +231,8 @@ def main():
         del sd, store
         roof_extra += bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof)
         roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
+        roof_extra += bench_decode(torch, B, synth, hbm_roof)
+        result["hbm_copy_ceiling_gbs"] = measured_copy_rate(torch)
         result["cpu_baseline"] = cpu_baseline(synth, cfg)
     result["roofline_extra"] = roof_extra
     print(json.dumps(result))
@@ -232,6 +248,13 @@ def run_case(torch, B, synth, case, iters):
             dst.copy_(src)
         torch.cuda.synchronize()
         print("case copy: %d launches of a %d-byte device copy" % (iters, src.numel()))
+        return
+    if case == "decode2":
+        run, _ = _decode_setup(torch, B, synth)
+        for _ in range(iters):
+            run()
+        torch.cuda.synchronize()
+        print("case decode2: %d calls" % iters)
         return
     if case == "offline5":
         cfg = synth.CONFIGS[5]
@@ -266,7 +289,8 @@ def run_case(torch, B, synth, case, iters):
     app = lambda: B.tr_kv_append(gs, k_q, v_q, q_pos, ck, cv, n_doc)
     att = lambda: B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
     asm(); app()
-    what = {"assemble": [asm], "attn": [att], "step": [asm, app, att]}[case[:-1]]
+    fused = lambda: B.tr_kv_assemble_append(sd, req.chunk_ids, offsets, req.pos_mode, k_q, v_q, q_pos, ck, cv)
+    what = {"assemble": [asm], "attn": [att], "step": [fused, att]}[case[:-1]]
     for _ in range(iters):
         for f in what:
             f()
@@ -334,6 +358,43 @@ def bench_config5(torch, B, synth, acct, mfma_roof):
     r = mfma_roof("tr_chunk_prefill_attn", cfg.name, flops, t, nbytes)
     r["note"] = "whole call: position table + key rotation + block-diagonal attention kernels"
     return [r]
+
+
+DECODE_BATCH, DECODE_KV = 64, 4096
+
+
+def _decode_setup(torch, B, synth):
+    sh = synth.CONFIGS[2].shape
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20241007)
+    rows = DECODE_BATCH * DECODE_KV
+    k = torch.randn((rows, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(sh.torch_dtype)
+    v = torch.randn((rows, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(sh.torch_dtype)
+    q = torch.randn((DECODE_BATCH, sh.n_q_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(sh.torch_dtype)
+    crs = np.arange(DECODE_BATCH + 1, dtype=np.int64) * DECODE_KV
+    q_pos = torch.full((DECODE_BATCH,), DECODE_KV - 1, dtype=torch.int32, device="cuda")
+    out = torch.empty_like(q)
+    ws = B.workspace(B.tr_decode_attn_workspace_size(gs, crs))
+    nbytes = (2 * rows * sh.n_kv_heads + 2 * DECODE_BATCH * sh.n_q_heads) * sh.head_dim * sh.elem_bytes
+    return (lambda: B.tr_decode_attn(gs, q, k, v, q_pos, crs, out, ws)), nbytes
+
+
+def bench_decode(torch, B, synth, hbm_roof):
+    """Decode step: one new token for each of 64 requests, 4096 cache rows each, Qwen2-7B shape (random cache
+    contents: the kernel's time does not depend on the values)."""
+    run, nbytes = _decode_setup(torch, B, synth)
+    t = _time_calls(torch, run, 20)
+    return [hbm_roof("tr_decode_attn", "decode-%dx%d-qwen2-7b" % (DECODE_BATCH, DECODE_KV), nbytes, t)]
+
+
+def measured_copy_rate(torch):
+    """What a plain device-to-device copy of 256 MiB reaches on this GPU (read + written bytes per second, GB/s):
+    the practical ceiling the HBM-bound kernels are up against, next to the published 8 TB/s."""
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    t = _time_calls(torch, lambda: dst.copy_(src), 10)
+    return round(2 * src.numel() / (t[0] * 1e-6) / 1e9, 1)
 
 
 def cpu_baseline(synth, cfg):
