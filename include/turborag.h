@@ -156,6 +156,23 @@ int tr_prefill_attn_batched(const tr_shape* shape, const void* q, const void* k,
                             const int64_t* cache_row_start /*host*/, int32_t n_req, void* out,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- the same prefill without waiting for the assembled document rows (Sec. 3.2, Sec. 3.4 steps 5-6) ---------
+ * Attention of the n_q query tokens over the request's retrieved chunks, read where they lie in the store, and
+ * over the query tokens' own rows, read from cache rows [n_doc, n_doc + n_q) of cache_k / cache_v (write them
+ * first with tr_kv_append, dst_row = n_doc = offsets[n_chunks]; the document rows of the cache are NOT read, so
+ * tr_kv_assemble may run at the same time on another stream).  Under TR_POS_REORDERED the stored keys sit at
+ * chunk-local positions; instead of turning each key by its chunk's offset the kernel turns the query by minus
+ * the offset, once per chunk, which gives the same scores (relative-position property of Eq. 3).  Result: what
+ * tr_prefill_attn computes on the assembled cache, up to the rounding of the re-rotated keys to the storage
+ * type, which this path skips.  chunk_ids, offsets, pos_mode as for tr_kv_assemble.  TR_BF16 only
+ * (TR_ERR_UNSUPPORTED otherwise, and for more than 95 non-empty chunks in a request). */
+size_t tr_prefill_attn_gather_workspace_size(const tr_store* store, const int32_t* chunk_ids /*host*/,
+                                             const int64_t* offsets /*host*/, int32_t n_chunks, int32_t pos_mode, int32_t n_q);
+int tr_prefill_attn_gather(const tr_store* store, const int32_t* chunk_ids /*host*/, const int64_t* offsets /*host*/,
+                           int32_t n_chunks, int32_t pos_mode, const void* q, const void* cache_k, const void* cache_v,
+                           const int32_t* q_pos /*device*/, int32_t n_q, int64_t cache_capacity_rows, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- decode step over the assembled cache (Sec. 3.4 step 7: answer generation reuses the cache) -----------
  * One new token per request, for a batch of requests: q, out: device [n_req, n_q_heads, head_dim]; q_pos:
  * device [n_req]; request r's cache is rows [cache_row_start[r], cache_row_start[r+1]) of k/v (host array),

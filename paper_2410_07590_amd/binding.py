@@ -24,6 +24,7 @@ EXPORTS = [
     "tr_kv_assemble", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched", "tr_kv_assemble_append",
     "tr_prefill_attn_workspace_size", "tr_prefill_attn",
     "tr_prefill_attn_batched_workspace_size", "tr_prefill_attn_batched",
+    "tr_prefill_attn_gather_workspace_size", "tr_prefill_attn_gather",
     "tr_decode_attn_workspace_size", "tr_decode_attn",
     "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
 ]
@@ -57,7 +58,8 @@ def lib():
         L = C.CDLL(_build.LIB)
         L.tr_last_error.restype = C.c_char_p
         for name in ("tr_prefill_attn_workspace_size", "tr_prefill_attn_batched_workspace_size",
-                     "tr_decode_attn_workspace_size", "tr_chunk_prefill_attn_workspace_size"):
+                     "tr_prefill_attn_gather_workspace_size", "tr_decode_attn_workspace_size",
+                     "tr_chunk_prefill_attn_workspace_size"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -197,6 +199,22 @@ def tr_prefill_attn_batched(shape, q, k, v, q_pos, cu_q, cache_row_start, out, w
     _check(lib().tr_prefill_attn_batched(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), cu_p, rs_p,
                                          C.c_int32(cu.size - 1), _dev(out), _dev(workspace), C.c_size_t(ws_bytes),
                                          _stream(stream)))
+
+
+def tr_prefill_attn_gather_workspace_size(store, chunk_ids, offsets, pos_mode, n_q):
+    ids, ids_p = _host(chunk_ids, np.int32)
+    off, off_p = _host(offsets, np.int64)
+    return int(lib().tr_prefill_attn_gather_workspace_size(store.handle, ids_p, off_p, C.c_int32(ids.size), C.c_int32(pos_mode),
+                                                           C.c_int32(n_q)))
+
+
+def tr_prefill_attn_gather(store, chunk_ids, offsets, pos_mode, q, cache_k, cache_v, q_pos, out, workspace=None, stream=None):
+    ids, ids_p = _host(chunk_ids, np.int32)
+    off, off_p = _host(offsets, np.int64)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().tr_prefill_attn_gather(store.handle, ids_p, off_p, C.c_int32(ids.size), C.c_int32(pos_mode), _dev(q), _dev(cache_k),
+                                        _dev(cache_v), _dev(q_pos), C.c_int32(q.shape[0]), C.c_int64(cache_k.shape[0]), _dev(out),
+                                        _dev(workspace), C.c_size_t(ws_bytes), _stream(stream)))
 
 
 def tr_decode_attn_workspace_size(shape, cache_row_start):

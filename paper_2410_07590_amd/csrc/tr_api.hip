@@ -552,6 +552,158 @@ extern "C" int tr_prefill_attn_batched(const tr_shape* shape, const void* q, con
     return run_prefix(shape, q, k, v, q_pos, reqs, out, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+// ---- query prefill that gathers the chunks itself (no assembled document rows needed) ---------------------------
+namespace {
+
+struct GatherPlan {
+    std::vector<TrGatherSeg> segs; // document segments, then the query-token segment
+    int64_t n_doc = 0;
+    int n_tiles = 0;
+    int row_tiles = 0;
+    int n_split = 1;
+    int tiles_per_split = 0;
+    int tok_per_tile = 0;
+};
+
+int plan_gather(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks, int32_t pos_mode,
+                int32_t n_q, GatherPlan* p)
+{
+    const tr_shape* sh = &store->shape;
+    if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
+    if (n_chunks > 0 && (!chunk_ids || !offsets)) return tr_fail(TR_ERR_INVALID_ARG, "chunk_ids or offsets is NULL");
+    const int n_store = (int)store->row_start.size() - 1;
+    int64_t off = 0;
+    int tiles = 0;
+    for (int i = 0; i < n_chunks; ++i) {
+        const int32_t c = chunk_ids[i];
+        if (c < 0 || c >= n_store) return tr_fail(TR_ERR_BAD_CHUNK_ID, "chunk_ids[%d] = %d outside [0, %d)", i, c, n_store);
+        if (offsets[i] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, the prefix sum of the chunk lengths is %lld", i, (long long)offsets[i], (long long)off);
+        const int64_t len = store->row_start[c + 1] - store->row_start[c];
+        if (len > 0) {
+            TrGatherSeg e;
+            e.src_row = (int32_t)store->row_start[c];
+            e.n_rows = (int32_t)len;
+            e.delta = pos_mode == TR_POS_REORDERED ? (int32_t)off : 0;
+            e.tile0 = tiles;
+            e.cache_row = (int32_t)off;
+            p->segs.push_back(e);
+            tiles += (int)((len + KEY_TILE - 1) / KEY_TILE);
+        }
+        off += len;
+    }
+    if (n_chunks > 0 && offsets[n_chunks] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, expected n_doc = %lld", n_chunks, (long long)offsets[n_chunks], (long long)off);
+    if (off + n_q > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "2^31 rows or more");
+    if ((int)p->segs.size() + 1 > TR_MAX_GATHER_SEG)
+        return tr_fail(TR_ERR_UNSUPPORTED, "%d non-empty chunks in one request, at most %d", (int)p->segs.size(), TR_MAX_GATHER_SEG - 1);
+    TrGatherSeg t;
+    t.src_row = (int32_t)off; // the query tokens sit behind the documents in the request's cache
+    t.n_rows = n_q;
+    t.delta = 0;
+    t.tile0 = tiles;
+    t.cache_row = (int32_t)off;
+    p->segs.push_back(t);
+    tiles += (n_q + KEY_TILE - 1) / KEY_TILE;
+    p->n_doc = off;
+    p->n_tiles = tiles;
+    const int g = sh->n_q_heads / sh->n_kv_heads;
+    p->tok_per_tile = 128 / g;
+    p->row_tiles = (n_q + p->tok_per_tile - 1) / p->tok_per_tile;
+    const int base_items = p->row_tiles * sh->n_kv_heads;
+    int want = base_items < TARGET_ITEMS ? (TARGET_ITEMS + base_items - 1) / base_items : 1;
+    if (want > MAX_SPLIT) want = MAX_SPLIT;
+    const int max_split = std::max(1, tiles / (MIN_SPLIT_KEYS / KEY_TILE));
+    if (want > max_split) want = max_split;
+    p->tiles_per_split = (tiles + want - 1) / want;
+    p->n_split = (tiles + p->tiles_per_split - 1) / p->tiles_per_split;
+    return TR_OK;
+}
+
+size_t gather_ws_bytes(const tr_shape* sh, const GatherPlan& p, int32_t n_q)
+{
+    if (p.n_split <= 1) return 0;
+    const size_t rows = (size_t)p.n_split * n_q * sh->n_q_heads;
+    return tr_align256(rows * sh->head_dim * 2) + tr_align256(rows * 8);
+}
+
+} // namespace
+
+extern "C" size_t tr_prefill_attn_gather_workspace_size(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets,
+                                                        int32_t n_chunks, int32_t pos_mode, int32_t n_q)
+{
+    if (!store || n_chunks < 0 || n_q <= 0) return 0;
+    GatherPlan p;
+    if (plan_gather(store, chunk_ids, offsets, n_chunks, pos_mode, n_q, &p)) return 0;
+    return gather_ws_bytes(&store->shape, p, n_q);
+}
+
+extern "C" int tr_prefill_attn_gather(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
+                                      int32_t pos_mode, const void* q, const void* cache_k, const void* cache_v,
+                                      const int32_t* q_pos, int32_t n_q, int64_t cache_capacity_rows, void* out,
+                                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    tr_clear_error();
+    if (!store) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn_gather: store is NULL");
+    if (n_chunks < 0 || n_q < 0) return tr_fail(TR_ERR_INVALID_ARG, "negative count");
+    const tr_shape* sh = &store->shape;
+    if (sh->dtype != TR_BF16) return tr_fail(TR_ERR_UNSUPPORTED, "tr_prefill_attn_gather is implemented for TR_BF16 only");
+    GatherPlan p;
+    int rc = plan_gather(store, chunk_ids, offsets, n_chunks, pos_mode, n_q, &p);
+    if (rc) return rc;
+    if (n_q == 0) return TR_OK;
+    if (!q || !cache_k || !cache_v || !q_pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn_gather: NULL pointer");
+    if (p.n_doc + n_q > cache_capacity_rows) return tr_fail(TR_ERR_BAD_PLAN, "the cache holds %lld rows, the query tokens end at row %lld", (long long)cache_capacity_rows, (long long)(p.n_doc + n_q));
+    const size_t need = gather_ws_bytes(sh, p, n_q);
+    if (need > 0) {
+        if (!workspace) return tr_fail(TR_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+        if (((uintptr_t)workspace & 255) != 0) return tr_fail(TR_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+        if (workspace_bytes < need) return tr_fail(TR_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    }
+    TrGatherArgs a;
+    memset(&a, 0, sizeof a);
+    a.q = q;
+    a.k_store = store->k;
+    a.v_store = store->v;
+    a.k_cache = cache_k;
+    a.v_cache = cache_v;
+    a.q_pos = q_pos;
+    a.out = out;
+    const size_t rows = (size_t)p.n_split * n_q * sh->n_q_heads;
+    a.ws_o = (_Float16*)workspace;
+    a.ws_ml = need ? (float*)((char*)workspace + tr_align256(rows * sh->head_dim * 2)) : nullptr;
+    a.n_q = n_q;
+    a.n_doc = (int32_t)p.n_doc;
+    a.n_seg = (int32_t)p.segs.size();
+    a.n_tiles_total = p.n_tiles;
+    a.n_split = p.n_split;
+    a.tiles_per_split = p.tiles_per_split;
+    a.row_tiles = p.row_tiles;
+    a.n_items = p.row_tiles * sh->n_kv_heads * p.n_split;
+    a.n_q_heads = sh->n_q_heads;
+    a.n_kv_heads = sh->n_kv_heads;
+    a.group = sh->n_q_heads / sh->n_kv_heads;
+    a.tok_per_tile = p.tok_per_tile;
+    a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)sh->head_dim));
+    double theta[64];
+    tr_fill_theta(sh, theta);
+    for (int m = 0; m < 64; ++m) a.theta_rev[m] = theta[m] / 6.283185307179586476925;
+    for (size_t i = 0; i < p.segs.size(); ++i) a.seg[i] = p.segs[i];
+    // the merge kernel reads the same partial layout as for tr_prefill_attn
+    TrPrefixArgs ca;
+    memset(&ca, 0, sizeof ca);
+    ca.out = out;
+    ca.ws_o = a.ws_o;
+    ca.ws_ml = a.ws_ml;
+    ca.n_seq = 1;
+    ca.n_q_heads = sh->n_q_heads;
+    ca.n_kv_heads = sh->n_kv_heads;
+    ca.group = a.group;
+    ca.seq[0].q_row0 = 0;
+    ca.seq[0].n_q = n_q;
+    ca.seq[0].n_split = p.n_split;
+    ca.seq[0].ws_row0 = 0;
+    return tr_launch_gather_attn(a, ca, sh->head_dim, (hipStream_t)stream);
+}
+
 // ---- decode step: one query token per request ---------------------------------------------------------------------
 namespace {
 int decode_cu(int32_t n_req, std::vector<int32_t>* cu)

@@ -63,7 +63,6 @@ struct RowCtx {
     int orow;    // q_tok * n_q_heads + head: row of q / out in units of head vectors
     int key_lo;  // first visible cache row
     int key_hi;  // last visible cache row
-    double pos;  // RoPE position id of the query token
 };
 
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -99,7 +98,7 @@ __device__ __forceinline__ int wave_min_i(int v)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int ROT_SLOTS = 8; // distinct tokens a wave's 32 packed rows can span when the GQA group is >= 4
+constexpr int ROT_SLOTS = 8; // token slots per rotation pass; covers a wave's 32 packed rows when the GQA group is >= 4
 
 // Issue the loads of this lane's raw fragments; rows that do not exist read row 0 and are zeroed later.
 template <int D>
@@ -117,29 +116,9 @@ __device__ __forceinline__ void rot_pair(uint32_t w, float cn, float sn, float s
     f[2 * p + 1] = (__bf16)(xb * cn + xa * sn);
 }
 
-// Every lane computes the angles of its own row: used when rows of a wave share few tokens (group < 4).
-template <int D>
-__device__ __forceinline__ void rotate_q_direct(const u32x4 (&raw)[D / 16], double pos, const double* theta_rev, int h,
-                                                bool valid, float sl2e, bf16x8 (&qf)[D / 16])
-{
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) {
-        bf16x8 f;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const double t0 = theta_rev[8 * ks + p], t1 = theta_rev[8 * ks + 4 + p];
-            double rev = pos * (h ? t1 : t0);
-            rev -= rint(rev);
-            const float x = (float)rev;
-            rot_pair(raw[ks][p], __builtin_amdgcn_cosf(x), __builtin_amdgcn_sinf(x), sl2e, valid, f, p);
-        }
-        qf[ks] = f;
-    }
-}
-
 // The g query heads of a token share its angles, so a wave's 32 rows need at most ROT_SLOTS x D/2 distinct
 // (cos, sin) pairs instead of 32 x D/2: the wave computes them once into a private LDS table, lane -> pair index,
-// one token slot (two for D = 64) per pass.  pos_lane: position id of slot (lane & 7).
+// one token slot (two for D = 64) per step.  pos_lane: position id of slot (lane & 7).
 // Table layout: slot j, pair m at byte j * 4 D + (((m >> 1) ^ 2 j) * 16) + (m & 1) * 8.
 template <int D>
 __device__ __forceinline__ void build_rot_table(LDS_AS char* tab, double th /* theta_rev[lane % (D/2)] */, int lane, int pos_lane)
@@ -176,6 +155,27 @@ __device__ __forceinline__ void rotate_q_shared(const u32x4 (&raw)[D / 16], LDS_
         rot_pair(raw[ks][2], cs1[0], cs1[1], sl2e, valid, f, 2);
         rot_pair(raw[ks][3], cs1[2], cs1[3], sl2e, valid, f, 3);
         qf[ks] = f;
+    }
+}
+
+// Rotated, scaled queries of a wave from their raw fragments.  slot: which of the wave's tokens this lane's row
+// belongs to (0 .. n_slots-1, n_slots wave-uniform); pos_of_slot(s): position id of the wave's token slot s (any
+// value for slots past the wave's last token).  Tokens go through the table ROT_SLOTS at a time: one pass when the
+// GQA group is >= 4, up to four for smaller groups.
+template <int D, class PosFn>
+__device__ __forceinline__ void rotate_queries(const u32x4 (&raw)[D / 16], LDS_AS char* tab, double th, int lane, int h, int slot,
+                                               int n_slots, bool valid, float sl2e, PosFn pos_of_slot, bf16x8 (&qf)[D / 16])
+{
+    n_slots = __builtin_amdgcn_readfirstlane(n_slots);
+    for (int p0 = 0; p0 < n_slots; p0 += ROT_SLOTS) {
+        build_rot_table<D>(tab, th, lane, pos_of_slot(p0 + (lane & (ROT_SLOTS - 1))));
+        const bool mine = (slot >= p0) && (slot < p0 + ROT_SLOTS);
+        bf16x8 f[D / 16];
+        rotate_q_shared<D>(raw, tab, mine ? slot - p0 : 0, h, valid, sl2e, f);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks)
+            if (mine || p0 == 0) qf[ks] = f[ks];
+        __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the table is read before the next pass (or a tile load) overwrites it
     }
 }
 
@@ -394,12 +394,12 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
 
 // Raw query loads, the first K/V tiles, then the rotation: the tile loads fly while the angles are computed.
 // Every ordinary load is issued before the tile loads, because loads return in order and one issued later
-// would make its consumer wait for the tiles.  pos_lane: position id of token slot (lane & 7) of this wave
-// (used when group >= 4); slot: this lane's slot.  The rotation table sits in stage NS-1, which no tile load
-// targets before the first barrier of the tile loop.
-template <int D, int NW, int NS>
+// would make its consumer wait for the tiles.  pos_lane: position id of token slot (lane & 7) of this wave, loaded by
+// the caller; pos_of_slot serves the later passes of small GQA groups.  The rotation table sits in stage NS-1, which
+// no tile load targets before the first barrier of the tile loop.
+template <int D, int NW, int NS, class PosFn>
 __device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-                                         const Walk& w, const RowCtx& rc, int group, int pos_lane, int slot,
+                                         const Walk& w, const RowCtx& rc, int pos_lane, int slot, int n_slots, PosFn pos_of_slot,
                                          const double* theta_rev, float sl2e, LDS_AS char* smem, bf16x8 (&qf)[D / 16])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5;
@@ -410,14 +410,9 @@ __device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __b
     __builtin_amdgcn_sched_barrier(0);
     issue_prologue<D, NW, NS>(k, v, w, smem, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
-    if (group >= 4) {
-        LDS_AS char* tab = smem + (NS - 1) * Geo<D>::STAGE_BYTES + wave * (ROT_SLOTS * 4 * D);
-        build_rot_table<D>(tab, th, lane, pos_lane);
-        rotate_q_shared<D>(raw, tab, slot, h, rc.valid, sl2e, qf);
-        __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the table reads are done before the stage is reused
-    } else {
-        rotate_q_direct<D>(raw, rc.pos, theta_rev, h, rc.valid, sl2e, qf);
-    }
+    LDS_AS char* tab = smem + (NS - 1) * Geo<D>::STAGE_BYTES + wave * (ROT_SLOTS * 4 * D);
+    rotate_queries<D>(raw, tab, th, lane, h, slot, n_slots, rc.valid, sl2e,
+                      [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
 }
 
 // Write the wave's 32 x D accumulator as rows: stage O^T through LDS (64 channels at a time) so that every
@@ -499,13 +494,12 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     rc.orow = (sd.q_row0 + tok_local) * a.n_q_heads + kvh * g + rl % g;
     rc.key_lo = sd.kv_row0;
     rc.key_hi = sd.kv_row0 + n_doc + tok_local;
-    // position ids: per token slot of the wave when the rotation table is shared, else per row
+    // position ids per token slot of the wave
     const int wave_tok0 = tile * tpt + (32 * wave) / g;
-    int pos_lane = 0;
-    rc.pos = 0.0;
-    if (g >= 4) pos_lane = a.q_pos[sd.q_row0 + min(wave_tok0 + (lane & (ROT_SLOTS - 1)), sd.n_q - 1)];
-    else if (rc.valid) rc.pos = (double)a.q_pos[sd.q_row0 + tok_local];
-    const int slot = min(rl / g - (32 * wave) / g, ROT_SLOTS - 1);
+    const int slot = min(rl / g - (32 * wave) / g, 31);
+    const int n_slots = (32 * wave + 31) / g - (32 * wave) / g + 1;
+    auto pos_of_slot = [&](int s) { return a.q_pos[sd.q_row0 + min(wave_tok0 + s, sd.n_q - 1)]; };
+    const int pos_lane = pos_of_slot(lane & (ROT_SLOTS - 1));
 
     const int first_tok = tile * tpt;
     const int last_tok = min(first_tok + tpt, sd.n_q) - 1;
@@ -514,8 +508,8 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     const Walk w = make_walk(sb, min(se, sd.kv_row0 + n_doc + last_tok + 1), sd.kv_row0 + sd.kv_len - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, g, pos_lane, slot, a.theta_rev,
-                        a.scale_log2e, smem, qf);
+    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
+                        a.theta_rev, a.scale_log2e, smem, qf);
 
     Acc<D> acc;
 #pragma unroll
@@ -537,6 +531,166 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
         const int64_t prow = (int64_t)sd.ws_row0 + (int64_t)(split * a.n_kv_heads + kvh) * rows_s + tok_local * g + rl % g;
         store_rows<D, true>(acc, l_tot, rc.valid, prow, a.ws_o, wave_buf, lane);
         // a split in which the row saw no key reports m = -inf so that the merge ignores it
+        if (rc.valid && h == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(l_tot > 0.0f ? acc.mref : -INFINITY, l_tot);
+    }
+}
+
+// ---- step 6 without a materialised cache: attention that gathers the chunks itself --------------------------------
+// The document keys are read straight from the store, where they are rotated at chunk-local positions.  Under
+// reordered positions the score needs R(off + t) k; since <R(p) q, R(off + t) k> = <R(p - off) q, R(t) k> (the
+// relative-position property behind Eq. 3), the kernel turns the QUERY by -off once per chunk instead of turning
+// every key.  The request's own query tokens are read from the cache rows that tr_kv_append wrote.  The walk is a
+// list of 64-key tiles, chunk by chunk; the last tile of a chunk may be partial (its missing keys are masked).
+constexpr int GATHER_NW = 4, GATHER_NS = 2;
+template <int D> constexpr int gather_lds_bytes() { return GATHER_NS * Geo<D>::STAGE_BYTES + GATHER_NW * ROT_SLOTS * 4 * D; }
+
+template <int D>
+__global__ __launch_bounds__(64 * GATHER_NW, 2) void gather_attn_kernel(const TrGatherArgs a)
+{
+    using G = Geo<D>;
+    constexpr int NW = GATHER_NW, NS = GATHER_NS;
+    extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+    LDS_AS char* smem = (LDS_AS char*)smem_raw;
+    const int item = xcd_remap(blockIdx.x, a.n_items);
+    const int tile = item % a.row_tiles;
+    const int rest = item / a.row_tiles;
+    const int split = rest % a.n_split;
+    const int kvh = rest / a.n_split;
+    const int g = a.group, tpt = a.tok_per_tile;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int i16 = lane & 15, colhalf = (lane >> 4) & 1;
+    const int rl = 32 * wave + c;
+    const int tok_local = tile * tpt + rl / g;
+    RowCtx rc;
+    rc.valid = (rl < tpt * g) && (tok_local < a.n_q);
+    rc.orow = tok_local * a.n_q_heads + kvh * g + rl % g;
+    rc.key_lo = 0;
+    rc.key_hi = a.n_doc + tok_local;
+    const int wave_tok0 = tile * tpt + (32 * wave) / g;
+    const int slot = min(rl / g - (32 * wave) / g, 31);
+    const int n_slots = (32 * wave + 31) / g - (32 * wave) / g + 1;
+    const int first_tok = tile * tpt;
+    const int last_tok = min(first_tok + tpt, a.n_q) - 1;
+
+    // this workgroup's tiles: a contiguous range of the request's tile list, cut at the causal end of its rows
+    const int tail = a.n_seg - 1;
+    const int g0 = split * a.tiles_per_split;
+    int g1 = min(g0 + a.tiles_per_split, a.n_tiles_total);
+    g1 = min(g1, a.seg[tail].tile0 + last_tok / KT + 1);
+    const int n_tiles = g1 > g0 ? g1 - g0 : 0;
+    int s_issue = 0;
+    while (s_issue + 1 < a.n_seg && a.seg[s_issue + 1].tile0 <= g0) ++s_issue;
+    int s_comp = s_issue;
+
+    const int64_t row_elems = (int64_t)a.n_kv_heads * D;
+    const int head_off = kvh * D;
+    auto issue = [&](int gt, int sg, LDS_AS char* stage) {
+        const TrGatherSeg e = a.seg[sg];
+        const int first = e.src_row + (gt - e.tile0) * KT;
+        const bool from_cache = sg == tail;
+        issue_tile<D, NW>((const __bf16*)(from_cache ? a.k_cache : a.k_store), (const __bf16*)(from_cache ? a.v_cache : a.v_store),
+                          row_elems, head_off, first, e.src_row + e.n_rows - 1, stage, wave, lane);
+    };
+
+    if (n_tiles > 0) issue(g0, s_issue, smem);
+    // The queries are rotated at the top of the tile loop whenever the chunk (hence the offset) changes, the first
+    // tile included.  The raw rows are fetched again each time rather than held in 32 registers through the loop:
+    // the change is rare (once per chunk) and the rows are in L2.
+    LDS_AS char* tab = smem + NS * G::STAGE_BYTES + wave * (ROT_SLOTS * 4 * D); // private to the wave, outside the ring
+    bf16x8 qf[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) qf[ks] = bf16x8{};
+    int cur_delta = INT32_MIN;
+
+    Acc<D> acc;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc.o[db][e] = 0.0f;
+    acc.mref = 0.0f;
+    acc.l = 0.0f;
+
+    const int wave_hi_max = wave_max_i(rc.valid ? rc.key_hi : INT32_MIN);
+    const int mask_hi_min = a.n_doc + first_tok;
+    int koff[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) koff[ks] = c * D * 2 + (((2 * ks + h) ^ G::kswz(c)) * 16);
+    int voff[D / 32];
+    {
+        const int r = 4 * h + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+            voff[db] = r * D * 2 + (4 * (db ^ G::vswz(r)) + 2 * colhalf + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
+    }
+
+    bf16x8 bpk[2][2];
+    for (int t = 0; t < n_tiles; ++t) {
+        const int gt = g0 + t;
+        while (s_comp + 1 < a.n_seg && a.seg[s_comp + 1].tile0 <= gt) ++s_comp;
+        const TrGatherSeg e = a.seg[s_comp];
+        if (e.delta != cur_delta) { // a new chunk: the queries turn to its offset
+            cur_delta = e.delta;
+            const double th = a.theta_rev[lane % (D / 2)];
+            const __bf16* qrow = (const __bf16*)a.q + (int64_t)(rc.valid ? rc.orow : 0) * D + 8 * h;
+            const int ns = __builtin_amdgcn_readfirstlane(n_slots);
+            for (int p0 = 0; p0 < ns; p0 += ROT_SLOTS) { // one pass when the GQA group is >= 4
+                build_rot_table<D>(tab, th, lane, a.q_pos[min(wave_tok0 + p0 + (lane & (ROT_SLOTS - 1)), a.n_q - 1)] - cur_delta);
+                const bool mine = (slot >= p0) && (slot < p0 + ROT_SLOTS);
+                LDS_AS const char* row = tab + (mine ? slot - p0 : 0) * (4 * D);
+                const int sw = 2 * (mine ? slot - p0 : 0);
+                // the raw fragments come in two halves so that they never hold more than 16 registers
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    u32x4 raw[D / 32];
+#pragma unroll
+                    for (int i = 0; i < D / 32; ++i) raw[i] = *(const u32x4*)(qrow + 16 * (half * (D / 32) + i));
+#pragma unroll
+                    for (int i = 0; i < D / 32; ++i) {
+                        const int ks = half * (D / 32) + i;
+                        const int ch = (2 * (2 * ks + h)) ^ sw;
+                        const f32x4 cs0 = *(LDS_AS const f32x4*)(row + ch * 16);
+                        const f32x4 cs1 = *(LDS_AS const f32x4*)(row + ch * 16 + 16);
+                        bf16x8 f;
+                        rot_pair(raw[i][0], cs0[0], cs0[1], a.scale_log2e, rc.valid, f, 0);
+                        rot_pair(raw[i][1], cs0[2], cs0[3], a.scale_log2e, rc.valid, f, 1);
+                        rot_pair(raw[i][2], cs1[0], cs1[1], a.scale_log2e, rc.valid, f, 2);
+                        rot_pair(raw[i][3], cs1[2], cs1[3], a.scale_log2e, rc.valid, f, 3);
+                        if (mine || p0 == 0) qf[ks] = f;
+                    }
+                }
+                __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the table is read before the next pass rewrites it
+            }
+        }
+        wait_vm<0>(); // two stages: tile t is the only load in flight here
+        __builtin_amdgcn_s_barrier();
+        if (t + 1 < n_tiles) {
+            while (s_issue + 1 < a.n_seg && a.seg[s_issue + 1].tile0 <= gt + 1) ++s_issue;
+            issue(gt + 1, s_issue, smem + ((t + 1) % NS) * G::STAGE_BYTES);
+        }
+        const int j = gt - e.tile0;
+        const int kt = e.cache_row + j * KT;                      // cache row the tile's first key stands for
+        const int last_valid = e.cache_row + min(e.n_rows, (j + 1) * KT) - 1;
+        if (kt <= wave_hi_max) {
+            LDS_AS const char* stage = smem + (t % NS) * G::STAGE_BYTES;
+            RowCtx rct = rc;
+            rct.key_hi = min(rc.key_hi, last_valid);
+            const bool need_mask = (kt + KT - 1 > mask_hi_min) || (last_valid < kt + KT - 1);
+            scores_softmax<D, 2>(stage, qf, rct, kt, need_mask, koff, h, acc, bpk);
+            weighted_values<D, 2>(stage + G::TILE_BYTES, bpk, voff, acc);
+        }
+    }
+
+    const float l_tot = acc.l + __shfl_xor(acc.l, 32);
+    __builtin_amdgcn_s_barrier(); // all waves are done with the K/V stages; reuse them as store staging
+    LDS_AS char* wave_buf = smem + wave * (32 * (64 * 4 + 16));
+    if (a.n_split == 1) {
+        store_rows<D, false>(acc, l_tot, rc.valid, (int64_t)rc.orow, a.out, wave_buf, lane);
+    } else {
+        const int rows_s = a.n_q * g;
+        const int64_t prow = (int64_t)(split * a.n_kv_heads + kvh) * rows_s + tok_local * g + rl % g;
+        store_rows<D, true>(acc, l_tot, rc.valid, prow, a.ws_o, wave_buf, lane);
         if (rc.valid && h == 0) *(float2*)(a.ws_ml + prow * 2) = make_float2(l_tot > 0.0f ? acc.mref : -INFINITY, l_tot);
     }
 }
@@ -584,11 +738,10 @@ __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPr
     rc.orow = (sd.q_row0 + tok_local) * a.n_q_heads + kvh * g + c % g;
     rc.key_lo = sd.kv_row0;
     rc.key_hi = sd.kv_row0 + n_doc + tok_local;
-    int pos_lane = 0;
-    rc.pos = 0.0;
-    if (g >= 4) pos_lane = a.q_pos[sd.q_row0 + min(tile * tpt + (lane & (ROT_SLOTS - 1)), sd.n_q - 1)];
-    else if (rc.valid) rc.pos = (double)a.q_pos[sd.q_row0 + tok_local];
-    const int slot = min(c / g, ROT_SLOTS - 1);
+    const int slot = min(c / g, 31);
+    const int n_slots = 31 / g + 1;
+    auto pos_of_slot = [&](int s) { return a.q_pos[sd.q_row0 + min(tile * tpt + s, sd.n_q - 1)]; };
+    const int pos_lane = pos_of_slot(lane & (ROT_SLOTS - 1));
 
     const int first_tok = tile * tpt;
     const int last_tok = min(first_tok + tpt, sd.n_q) - 1;
@@ -612,13 +765,10 @@ __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPr
     if (n_tiles > 0) issue_tile<D, NW, SHORT_KT>(kp, vp, row_elems, head_off, kt_begin, key_clamp, smem, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
     bf16x8 qf[D / 16];
-    if (g >= 4) {
+    {
         LDS_AS char* tab = smem + STAGE + wave * (ROT_SLOTS * 4 * D); // stage 1 is free until the first barrier
-        build_rot_table<D>(tab, th, lane, pos_lane);
-        rotate_q_shared<D>(raw, tab, slot, h, rc.valid, a.scale_log2e, qf);
-        __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0)
-    } else {
-        rotate_q_direct<D>(raw, rc.pos, a.theta_rev, h, rc.valid, a.scale_log2e, qf);
+        rotate_queries<D>(raw, tab, th, lane, h, slot, n_slots, rc.valid, a.scale_log2e,
+                          [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
     }
 
     Acc<D> acc;
@@ -842,11 +992,12 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     rc.orow = t * a.n_q_heads + kvh * g + rl % g;
     rc.key_lo = rc.valid ? chunk_start(a.tok_start, t) : 0;
     rc.key_hi = t;
-    rc.pos = (double)(t - rc.key_lo);
-    // chunk-local position of token slot (lane & 7) of this wave
-    const int t_slot = min(tile * tpt + (32 * wave) / g + (lane & (ROT_SLOTS - 1)), T - 1);
-    const int pos_lane = t_slot - chunk_start(a.tok_start, t_slot);
-    const int slot = min(rl / g - (32 * wave) / g, ROT_SLOTS - 1);
+    // chunk-local position of each token slot of this wave
+    const int wave_t0 = tile * tpt + (32 * wave) / g;
+    auto pos_of_slot = [&](int s) { const int ts = min(wave_t0 + s, T - 1); return ts - chunk_start(a.tok_start, ts); };
+    const int pos_lane = pos_of_slot(lane & (ROT_SLOTS - 1));
+    const int slot = min(rl / g - (32 * wave) / g, 31);
+    const int n_slots = (32 * wave + 31) / g - (32 * wave) / g + 1;
 
     const int t_first = tile * tpt;
     const int t_last = min(t_first + tpt, T) - 1;
@@ -855,8 +1006,8 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     const Walk w = make_walk(lo_first, t_last + 1, T - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, g, pos_lane, slot, a.theta_rev,
-                        a.scale_log2e, smem, qf);
+    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
+                        a.theta_rev, a.scale_log2e, smem, qf);
 
     Acc<D> acc;
 #pragma unroll
@@ -913,6 +1064,22 @@ int launch_short(const TrPrefixArgs& a, hipStream_t s)
     return TR_OK;
 }
 
+template <int D>
+int launch_gather(const TrGatherArgs& a, hipStream_t s)
+{
+    auto kern = gather_attn_kernel<D>;
+    constexpr int staging = GATHER_NW * 32 * (64 * 4 + 16);
+    constexpr int lds = gather_lds_bytes<D>() > staging ? gather_lds_bytes<D>() : staging;
+    static bool configured = false;
+    if (!configured) {
+        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.n_items), dim3(64 * GATHER_NW), lds, s, a);
+    TR_HIP(hipGetLastError());
+    return TR_OK;
+}
+
 template <int D, int NW, int NS>
 int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
 {
@@ -945,6 +1112,21 @@ int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool
         const int blocks = (total_rows + rows_per_block - 1) / rows_per_block;
         if (head_dim == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3(blocks), dim3(256), 0, s, a, total_rows);
         else hipLaunchKernelGGL(combine_kernel<64>, dim3(blocks), dim3(256), 0, s, a, total_rows);
+        TR_HIP(hipGetLastError());
+    }
+    return TR_OK;
+}
+
+int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_args, int head_dim, hipStream_t s)
+{
+    if (a.n_items <= 0) return TR_OK;
+    int rc = head_dim == 128 ? launch_gather<128>(a, s) : launch_gather<64>(a, s);
+    if (rc) return rc;
+    if (a.n_split > 1) {
+        const int total_rows = a.n_q * a.n_q_heads;
+        const int blocks = (total_rows + 7) / 8;
+        if (head_dim == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3(blocks), dim3(256), 0, s, combine_args, total_rows);
+        else hipLaunchKernelGGL(combine_kernel<64>, dim3(blocks), dim3(256), 0, s, combine_args, total_rows);
         TR_HIP(hipGetLastError());
     }
     return TR_OK;

@@ -124,6 +124,45 @@ struct TrPrefixArgs {
     TrSeqDesc seq[TR_MAX_SEQ];
 };
 
+// gather attention: the keys of one request, read where they lie.  A segment is one retrieved chunk in the store
+// (rows src_row .. +n_rows, keys stored at chunk-local positions, delta = the chunk's offset under reordered
+// positions, else 0), or, last, the request's own query tokens in its cache (delta 0).
+struct TrGatherSeg {
+    int32_t src_row;
+    int32_t n_rows;
+    int32_t delta;
+    int32_t tile0;     // first 64-key tile of the segment in the request's tile list
+    int32_t cache_row; // cache row its first key would have after assembly
+};
+#define TR_MAX_GATHER_SEG 96
+struct TrGatherArgs {
+    const void* q;
+    const void* k_store;
+    const void* v_store;
+    const void* k_cache;
+    const void* v_cache;
+    const int32_t* q_pos;
+    void* out;
+    _Float16* ws_o;
+    float* ws_ml;
+    int32_t n_q;
+    int32_t n_doc;
+    int32_t n_seg;           // segments, the query-token segment included (it is the last)
+    int32_t n_tiles_total;
+    int32_t n_split;
+    int32_t tiles_per_split;
+    int32_t row_tiles;
+    int32_t n_items;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t group;
+    int32_t tok_per_tile;
+    float scale_log2e;
+    float pad_;
+    double theta_rev[64];
+    TrGatherSeg seg[TR_MAX_GATHER_SEG];
+};
+
 struct TrBlockDiagArgs {
     const void* q;
     const void* k; // rotated keys K'
@@ -151,4 +190,5 @@ int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* t
 int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int max_chunk_len, int32_t* tok_start,
                         const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s);
 int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s);
+int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_args, int head_dim, hipStream_t s);
 int tr_launch_blockdiag_attn_f32(const TrBlockDiagArgs& a, int head_dim, hipStream_t s);

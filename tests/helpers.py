@@ -88,3 +88,33 @@ def check_request(B, sh, store, store_dev, req, rows=None, k_mismatch_frac=1e-5)
     assert np.isfinite(got).all()
     assert err <= tol_for(sh), "attention max abs err %.3e" % err
     return err, n_bad
+
+
+def run_request_gather_gpu(B, sh, store_dev, req):
+    """The same request through tr_prefill_attn_gather: only the query tokens' rows of the cache are written (append); the
+    document rows stay NaN, which shows that the attention reads the documents from the store."""
+    gs = store_dev.shape
+    offsets, _ = B.tr_plan(store_dev, req.chunk_ids, req.pos_mode, want_pos_ids=False)
+    n_doc = int(offsets[-1])
+    kv_len = n_doc + req.n_q
+    dt = sh.torch_dtype
+    cache_k = torch.full((kv_len, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=dt, device="cuda")
+    cache_v = torch.full_like(cache_k, float("nan"))
+    q_pos = torch.from_numpy(req.q_pos).cuda()
+    B.tr_kv_append(gs, req.k_q.cuda(), req.v_q.cuda(), q_pos, cache_k, cache_v, n_doc)
+    out = torch.full((req.n_q, sh.n_q_heads, sh.head_dim), float("nan"), dtype=dt, device="cuda")
+    ws = B.workspace(B.tr_prefill_attn_gather_workspace_size(store_dev, req.chunk_ids, offsets, req.pos_mode, req.n_q))
+    B.tr_prefill_attn_gather(store_dev, req.chunk_ids, offsets, req.pos_mode, req.q.cuda(), cache_k, cache_v, q_pos, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+def check_request_gather(B, sh, store, store_dev, req, rows=None):
+    got = to_f64(run_request_gather_gpu(B, sh, store_dev, req))
+    o = run_request_oracle(sh, store, req, rows)
+    if rows is not None:
+        got = got[np.asarray(rows)]
+    assert np.isfinite(got).all()
+    err = float(np.abs(got - o["out"]).max()) if got.size else 0.0
+    assert err <= tol_for(sh), "gather attention max abs err %.3e" % err
+    return err

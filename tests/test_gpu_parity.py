@@ -66,6 +66,8 @@ def test_ragged_bf16(B, case, mode):
                         synth.normal_tensor(rng, (n_q, hkv, d), sh.torch_dtype), q_pos, sum(sel), sel)
     err, n_bad = H.check_request(B, sh, store, sd, req)
     print("ragged %d mode %d: max abs err %.3e" % (case, mode, err))
+    # the same request with the attention reading the chunks from the store (queries turned per chunk)
+    print("   gather attention: max abs err %.3e" % H.check_request_gather(B, sh, store, sd, req))
 
 
 def test_no_documents_and_noops(B):
@@ -213,6 +215,39 @@ def test_config3_full_batched(B):
     sd = _store_dev(B, cfg.shape, store)
     reqs = synth.make_requests(cfg, store)
     print("config3: max abs err %.3e (4 sampled query tokens per request)" % _check_batched(B, cfg, store, sd, reqs, rows_per_req=4))
+
+
+# ---- gather attention: the prefill that reads the chunks where they lie ------------------------------------------
+def test_gather_attention_config2_full(B):
+    cfg = synth.CONFIGS[2]
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    req = synth.make_requests(cfg, store)[0]
+    print("config2 gather attention: max abs err %.3e" % H.check_request_gather(B, cfg.shape, store, sd, req))
+
+
+def test_gather_attention_config4_sampled_rows(B):
+    cfg = synth.CONFIGS[4]
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    req = synth.make_requests(cfg, store)[0]
+    rows = np.array([0, 1, 63, 64, 127, 128, 200, 255], np.int32)
+    print("config4 gather attention: max abs err %.3e on %d sampled tokens" % (H.check_request_gather(B, cfg.shape, store, sd, req, rows), rows.size))
+
+
+def test_gather_attention_without_documents_and_composite_batch(B):
+    """No chunks at all (plain causal attention over the query tokens), and the requests of a scaled configuration 3
+    one by one (both position schemes, ragged chunk lengths, partial last tiles)."""
+    cfg = synth.scaled(synth.CONFIGS[3], store_chunks=40, chunk_len_lo=1, chunk_len_hi=150, n_requests=6,
+                       chunks_per_request=4, n_q_lo=1, n_q_hi=90)
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    reqs = synth.make_requests(cfg, store)
+    worst = max(H.check_request_gather(B, cfg.shape, store, sd, r) for r in reqs)
+    r0 = reqs[0]
+    none = synth.Request(np.zeros(0, np.int32), r0.pos_mode, r0.n_q, r0.q, r0.k_q, r0.v_q, np.arange(r0.n_q, dtype=np.int32), 0, [])
+    worst = max(worst, H.check_request_gather(B, cfg.shape, store, sd, none))
+    print("gather attention, scaled configuration 3 and no documents: max abs err %.3e" % worst)
 
 
 # ---- decode step (Sec. 3.4 step 7): one new token per request over its assembled cache ---------------------------
