@@ -96,6 +96,16 @@ def _stream(stream):
     return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
 
 
+def _dev_or_pinned(t):
+    """Device tensor, or a pinned host tensor (its address is valid on the device: a host-resident store)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        assert t.is_pinned() and t.is_contiguous(), "a host-resident store must be pinned, contiguous memory"
+        return C.c_void_p(t.data_ptr())
+    return _dev(t)
+
+
 class Store:
     """Owns a tr_store handle; keeps the store tensors alive."""
 
@@ -104,8 +114,7 @@ class Store:
         rs, rs_p = _host(chunk_row_start, np.int64)
         self.row_start = rs
         self.handle = C.c_void_p(0)
-        _check(lib().tr_store_create(C.byref(shape), _dev(k_store) if k_store is not None else None,
-                                     _dev(v_store) if v_store is not None else None, rs_p,
+        _check(lib().tr_store_create(C.byref(shape), _dev_or_pinned(k_store), _dev_or_pinned(v_store), rs_p,
                                      C.c_int32(rs.size - 1), C.byref(self.handle)))
 
     def close(self):

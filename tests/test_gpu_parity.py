@@ -217,6 +217,30 @@ def test_config3_full_batched(B):
     print("config3: max abs err %.3e (4 sampled query tokens per request)" % _check_batched(B, cfg, store, sd, reqs, rows_per_req=4))
 
 
+# ---- host-resident store: the assemble kernel reads pinned host memory across PCIe --------------------------------
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+def test_host_resident_store_assembles_the_same_bytes(B, mode):
+    cfg = synth.scaled(synth.CONFIGS[2], store_chunks=24, chunks_per_request=8, n_q_lo=9, n_q_hi=9)
+    sh = cfg.shape
+    store = synth.make_store(cfg)
+    req = synth.make_requests(cfg, store, pos_mode=mode)[0]
+    sd_dev = _store_dev(B, sh, store)
+    sd_host = B.Store(H.gpu_shape(B, sh), store.k.pin_memory(), store.v.pin_memory(), store.row_start)
+    outs = []
+    for sd in (sd_dev, sd_host):
+        offsets, _ = B.tr_plan(sd, req.chunk_ids, mode, want_pos_ids=False)
+        n_doc = int(offsets[-1])
+        ck = torch.full((n_doc + req.n_q, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=sh.torch_dtype, device="cuda")
+        cv = torch.full_like(ck, float("nan"))
+        B.tr_kv_assemble_append(sd, req.chunk_ids, offsets, mode, req.k_q.cuda(), req.v_q.cuda(), torch.from_numpy(req.q_pos).cuda(), ck, cv)
+        torch.cuda.synchronize()
+        outs.append((H.bits(ck.cpu()), H.bits(cv.cpu())))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    o = H.run_request_oracle(sh, store, req, rows=np.zeros(1, np.int32))
+    H.assert_same_bits(outs[1][1], o["v_cache_st"], "V assembled from the host store")
+    H.assert_same_bits(outs[1][0], o["k_cache_st"], "K assembled from the host store", 1e-5)
+
+
 # ---- gather attention: the prefill that reads the chunks where they lie ------------------------------------------
 def test_gather_attention_config2_full(B):
     cfg = synth.CONFIGS[2]
