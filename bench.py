@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--no-extra", action="store_true", help="skip configurations 4/5 and the CPU baseline")
     ap.add_argument("--no-graph", action="store_true", help="time the eager loop instead of a HIP graph replay")
+    ap.add_argument("--host-store", action="store_true",
+                    help="also time the path with the chunk store in pinned host memory (PCIe-bound; kept out of the default "
+                         "run so that its slow launches of the same kernels do not blur the kernel trace)")
     ap.add_argument("--case", default=None,
                     help="profiling aid: run only one kernel path --iters times, eagerly, and print nothing but a note "
                          "(step2, assemble2, attn2, assemble4, attn4, offline5, decode2, copy)")
@@ -232,7 +235,8 @@ def main():
         roof_extra += bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof)
         roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
         roof_extra += bench_decode(torch, B, synth, hbm_roof)
-        roof_extra += bench_host_store(torch, B, synth, acct)
+        if args.host_store:
+            roof_extra += bench_host_store(torch, B, synth, acct)
         result["hbm_copy_ceiling_gbs"] = measured_copy_rate(torch)
         result["cpu_baseline"] = cpu_baseline(synth, cfg)
     result["roofline_extra"] = roof_extra
