@@ -233,6 +233,7 @@ def main():
     if not args.no_extra:
         del sd, store
         roof_extra += bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof)
+        roof_extra += bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof)
         roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
         roof_extra += bench_decode(torch, B, synth, hbm_roof)
         if args.host_store:
@@ -339,6 +340,43 @@ def bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof):
     return [hbm_roof("tr_kv_assemble", cfg.name, acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb), t_asm),
             mfma_roof("tr_prefill_attn", cfg.name, acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_prefix(req.n_q, kv_len)),
                       t_att, acct.prefill_attn_bytes(req.n_q, kv_len, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb))]
+
+
+def bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof):
+    """Batched serving: 16 requests x 10 chunks (bounded Zipf ids over 1000 chunks of 256..1024 rows), 32..128 query
+    tokens each, composite and reordered positions mixed; one launch per stage for the whole batch."""
+    cfg = synth.CONFIGS[3]
+    sh = cfg.shape
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    store = synth.make_store(cfg)
+    sd = B.Store(gs, store.k.cuda(), store.v.cuda(), store.row_start)
+    reqs = synth.make_requests(cfg, store)
+    ids = np.concatenate([r.chunk_ids for r in reqs]).astype(np.int32)
+    cu_chunks = np.concatenate([[0], np.cumsum([r.chunk_ids.size for r in reqs])]).astype(np.int32)
+    modes = np.array([r.pos_mode for r in reqs], np.int32)
+    crs = np.concatenate([[0], np.cumsum([r.n_doc + r.n_q for r in reqs])]).astype(np.int64)
+    cu_q = np.concatenate([[0], np.cumsum([r.n_q for r in reqs])]).astype(np.int32)
+    total = int(crs[-1])
+    ck = torch.empty((total, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda")
+    cv = torch.empty_like(ck)
+    q = torch.cat([r.q for r in reqs]).cuda()
+    k_q = torch.cat([r.k_q for r in reqs]).cuda()
+    v_q = torch.cat([r.v_q for r in reqs]).cuda()
+    q_pos = torch.from_numpy(np.concatenate([r.q_pos for r in reqs]).astype(np.int32)).cuda()
+    out = torch.empty_like(q)
+    ws = B.workspace(B.tr_prefill_attn_batched_workspace_size(gs, cu_q, crs))
+    asm = lambda: B.tr_kv_assemble_batched(sd, ids, cu_chunks, modes, crs, ck, cv)
+    app = lambda: B.tr_kv_append_batched(gs, k_q, v_q, q_pos, cu_q, crs, ck, cv)
+    att = lambda: B.tr_prefill_attn_batched(gs, q, ck, cv, q_pos, cu_q, crs, out, ws)
+    asm(); app()
+    t_asm, t_app, t_att = _time_calls(torch, asm, 20), _time_calls(torch, app, 30), _time_calls(torch, att, 30)
+    eb = sh.elem_bytes
+    n_doc = sum(r.n_doc for r in reqs)
+    flops = sum(acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_prefix(r.n_q, r.n_doc + r.n_q)) for r in reqs)
+    nbytes = sum(acct.prefill_attn_bytes(r.n_q, r.n_doc + r.n_q, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb) for r in reqs)
+    return [hbm_roof("tr_kv_assemble_batched", cfg.name, acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb), t_asm),
+            {"kernel": "tr_kv_append_batched", "workload": cfg.name, "avg_us": round(t_app[0], 2), "median_us": round(t_app[1], 2)},
+            mfma_roof("tr_prefill_attn_batched", cfg.name, flops, t_att, nbytes)]
 
 
 def bench_config5(torch, B, synth, acct, mfma_roof):

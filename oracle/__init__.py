@@ -161,6 +161,41 @@ def attn_blockdiag(q_rot, k_rot, v, cu, rows=None):
     return out
 
 
+def attn_rows(q_rot, k_rot, v, lo, rows=None):
+    """Attention over a packed sequence where token t sees rows lo[t] .. t (documents: their own chunk; query and
+    answer tokens: everything before them), Sec. 3.2 / Sec. 3.3."""
+    q_rot, k_rot, v = _c(q_rot, np.float64), _c(k_rot, np.float64), _c(v, np.float64)
+    T, n_qh, d = q_rot.shape
+    _, n_kv, _ = k_rot.shape
+    lo = _c(lo, np.int32)
+    assert lo.shape == (T,) and (lo >= 0).all() and (lo <= np.arange(T)).all()
+    rows = np.arange(T, dtype=np.int32) if rows is None else _c(rows, np.int32)
+    out = np.empty((rows.size, n_qh, d), np.float64)
+    lib().orc_attn_rows(_p(q_rot), _p(k_rot), _p(v), _p(lo), C.c_int64(T), C.c_int(n_qh), C.c_int(n_kv), C.c_int(d),
+                        _p(rows), C.c_int(rows.size), _p(out))
+    return out
+
+
+def sequence_plan(chunk_lens, n_tail, pos_mode, tail_start=None):
+    """Visible-range starts and position ids of a packed training/prefill sequence [chunk_1 .. chunk_k, tail]
+    (Sec. 3.2, Sec. 3.3): a document token sees its own chunk up to itself, a tail (query/answer) token sees
+    everything before it; ids are chunk-local (composite) or run on (reordered); the tail's ids start at
+    tail_start (default: longest chunk under composite positions, n_doc under reordered positions)."""
+    chunk_lens = [int(l) for l in chunk_lens]
+    n_doc = sum(chunk_lens)
+    lo = np.zeros(n_doc + n_tail, np.int32)
+    pos = np.zeros(n_doc + n_tail, np.int32)
+    off = 0
+    for l in chunk_lens:
+        lo[off:off + l] = off
+        pos[off:off + l] = np.arange(l) + (off if pos_mode == POS_REORDERED else 0)
+        off += l
+    if tail_start is None:
+        tail_start = n_doc if pos_mode == POS_REORDERED else (max(chunk_lens) if chunk_lens else 0)
+    pos[n_doc:] = tail_start + np.arange(n_tail)
+    return lo, pos
+
+
 # ---- the pipeline, steps chained in the paper's order ---------------------------------------------
 
 def local_positions(cu):
@@ -214,5 +249,21 @@ def offline_chunk_prefill(q, k, v, cu, base, layout=ROPE_INTERLEAVED, rows=None,
         k_rot = widen(res["k_rot_st"])
     q_rot = rope(q, lp, base, layout)
     res["out"] = attn_blockdiag(q_rot, k_rot, widen(v), cu, rows)
+    res["k_rot"] = k_rot
+    return res
+
+
+def masked_prefill(q, k, v, lo, pos, base, layout=ROPE_INTERLEAVED, rows=None, storage_rounding=True):
+    """One pass over a packed sequence: rotate q, k at pos (Eq. 3), token t attends rows lo[t] .. t.
+
+    Returns dict(out, k_rot[, k_rot_st])."""
+    dt = _dtype_of(np.asarray(k))
+    k_rot = rope(k, pos, base, layout)
+    res = {}
+    if storage_rounding:
+        res["k_rot_st"] = round_to(k_rot, dt)
+        k_rot = widen(res["k_rot_st"])
+    q_rot = rope(q, pos, base, layout)
+    res["out"] = attn_rows(q_rot, k_rot, widen(v), lo, rows)
     res["k_rot"] = k_rot
     return res

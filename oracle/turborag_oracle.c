@@ -298,6 +298,29 @@ void orc_attn_blockdiag(const double* q_rot, const double* k_rot, const double* 
     }
 }
 
+/* ---- one pass over a packed sequence with a per-token visible range (Sec. 3.3: fine-tuning uses the masks and
+ * position ids of inference; Sec. 3.2 independent attention for the documents, full attention for the query).
+ * Token t sees rows lo[t] .. t.  q_rot, k_rot are already rotated at the tokens' position ids.
+ * rows[] lists the packed token indices to compute: out [n_rows, n_qh, d]. */
+void orc_attn_rows(const double* q_rot, const double* k_rot, const double* v, const int32_t* lo, int64_t total,
+                   int n_qh, int n_kv, int d, const int32_t* rows, int n_rows, double* out)
+{
+    int g = n_qh / n_kv;
+    int64_t work = (int64_t)n_rows * n_qh;
+#pragma omp parallel
+    {
+        double* scratch = (double*)malloc(sizeof(double) * (size_t)(total > 0 ? total : 1));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t w = 0; w < work; ++w) {
+            int r = (int)(w / n_qh), h = (int)(w % n_qh);
+            int t = rows[r];
+            attend_row(q_rot + ((int64_t)t * n_qh + h) * d, k_rot, v, n_kv, h / g, d,
+                       lo[t], t, scratch, out + ((int64_t)r * n_qh + h) * d);
+        }
+        free(scratch);
+    }
+}
+
 /* Number of OpenMP threads the attention loops will use. */
 int orc_num_threads(void)
 {

@@ -313,6 +313,18 @@ def test_decode_full_batch64_kv4k(B):
     print("decode 64 x 4097: max abs err %.3e" % _check_batched(B, cfg, store, sd, reqs, decode=True))
 
 
+def test_more_requests_than_one_launch_describes(B):
+    """70 requests: the request descriptors travel in the kernel arguments, 64 per launch, so this takes two launches of
+    each kernel; once as a decode batch, once as a batched prefill with short queries."""
+    for n_q_hi, decode in ((1, True), (6, False)):
+        cfg = synth.scaled(synth.CONFIGS[3], store_chunks=30, chunk_len_lo=5, chunk_len_hi=60, n_requests=70,
+                           chunks_per_request=2, n_q_lo=1, n_q_hi=n_q_hi)
+        store = synth.make_store(cfg)
+        sd = _store_dev(B, cfg.shape, store)
+        reqs = synth.make_requests(cfg, store)
+        print("70 requests (decode=%s): max abs err %.3e" % (decode, _check_batched(B, cfg, store, sd, reqs, decode=decode)))
+
+
 def test_short_query_kernel_with_causal_rows(B, monkeypatch):
     """The key-splitting kernel forced onto queries of up to 40 tokens: several row tiles, causal mask among them."""
     monkeypatch.setenv("TR_WG_ROWS", "32")
