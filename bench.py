@@ -235,6 +235,7 @@ def main():
         roof_extra += bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof)
         roof_extra += bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof)
         roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
+        roof_extra += bench_sequence(torch, B, synth, acct, mfma_roof)
         roof_extra += bench_decode(torch, B, synth, hbm_roof)
         if args.host_store:
             roof_extra += bench_host_store(torch, B, synth, acct)
@@ -400,6 +401,32 @@ def bench_config5(torch, B, synth, acct, mfma_roof):
     nbytes = acct.chunk_prefill_bytes(T, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.elem_bytes)
     r = mfma_roof("tr_chunk_prefill_attn", cfg.name, flops, t, nbytes)
     r["note"] = "whole call: position table + key rotation + block-diagonal attention kernels"
+    return [r]
+
+
+def bench_sequence(torch, B, synth, acct, mfma_roof):
+    """The fine-tuning / whole-prefill form of configuration 4 in one pass: 32 chunks x 1024 tokens that attend
+    inside their own chunk, then 256 query tokens that attend everything (reordered position ids)."""
+    cfg = synth.CONFIGS[4]
+    sh = cfg.shape
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    lens, n_tail = [1024] * 32, 256
+    seg, pos = B.tr_sequence_plan(lens, n_tail, synth.POS_REORDERED)
+    T = seg.size
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20241011)
+    mk = lambda h: torch.randn((T, h, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(sh.torch_dtype)
+    q, k, v = mk(sh.n_q_heads), mk(sh.n_kv_heads), mk(sh.n_kv_heads)
+    out, k_rot = torch.empty_like(q), torch.empty_like(k)
+    seg_d, pos_d = torch.from_numpy(seg).cuda(), torch.from_numpy(pos).cuda()
+    run = lambda: B.tr_sequence_prefill_attn(gs, q, k, v, seg_d, pos_d, out, k_rot)
+    t = _time_calls(torch, run, 10)
+    n_doc = sum(lens)
+    pairs = acct.visible_pairs_blockdiag(lens) + acct.visible_pairs_prefix(n_tail, n_doc + n_tail)
+    r = mfma_roof("tr_sequence_prefill_attn", "32x1024-chunks-plus-256-query-llama3-8b",
+                  acct.attn_flops(sh.n_q_heads, sh.head_dim, pairs), t,
+                  acct.chunk_prefill_bytes(T, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.elem_bytes))
+    r["note"] = "whole call: key rotation at the position ids + one attention pass over documents and query"
     return [r]
 
 

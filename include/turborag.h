@@ -201,6 +201,22 @@ int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const void* k, c
                           int32_t max_chunk_len, void* out, void* k_rot_out,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- one pass over a packed sequence [chunk_1 .. chunk_k, tail] (Sec. 3.3: fine-tuning runs with the attention
+ * mask and position ids of inference; also a whole prefill, documents and query, in one call) ---------------------
+ * tr_sequence_plan (host): token t of chunk c gets seg_start = first row of c and pos = t - start (composite) or t
+ * (reordered) (Sec. 3.2); the n_tail query/answer tokens get seg_start = 0 and pos = tail_start + i, where
+ * tail_start < 0 selects the default (the longest chunk's length under composite positions, n_doc under reordered).
+ * seg_start, pos: host int32 arrays of `capacity` entries; TR_ERR_BAD_PLAN if the sequence is longer.
+ * tr_sequence_prefill_attn: q [T, n_q_heads, d], k, v [T, n_kv_heads, d] raw, seg_start, pos device int32 [T]
+ * (0 <= seg_start[t] <= t; values outside are clamped).  k_rot_out <- R(pos[t]) k[t] (fp64, one rounding; required,
+ * may alias k); token t attends rows seg_start[t] .. t of k_rot_out / v with the query rotated at pos[t];
+ * out [T, n_q_heads, d].  With seg_start = chunk starts and chunk-local pos this is tr_chunk_prefill_attn. */
+int tr_sequence_plan(const int32_t* chunk_lens /*host*/, int32_t n_chunks, int32_t n_tail, int32_t pos_mode, int32_t tail_start,
+                     int32_t* seg_start /*host out*/, int32_t* pos /*host out*/, int64_t capacity);
+int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v,
+                             const int32_t* seg_start /*device*/, const int32_t* pos /*device*/, int64_t total_tokens,
+                             void* out, void* k_rot_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

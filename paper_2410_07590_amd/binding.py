@@ -27,6 +27,7 @@ EXPORTS = [
     "tr_prefill_attn_gather_workspace_size", "tr_prefill_attn_gather",
     "tr_decode_attn_workspace_size", "tr_decode_attn",
     "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
+    "tr_sequence_plan", "tr_sequence_prefill_attn",
 ]
 
 
@@ -248,6 +249,22 @@ def tr_chunk_prefill_attn(shape, q, k, v, cu_chunk_lens, n_chunks, max_chunk_len
                                        C.c_int32(n_chunks), C.c_int64(q.shape[0]), C.c_int32(max_chunk_len),
                                        _dev(out), _dev(k_rot_out), _dev(workspace), C.c_size_t(ws_bytes),
                                        _stream(stream)))
+
+
+def tr_sequence_plan(chunk_lens, n_tail, pos_mode, tail_start=-1):
+    """Returns (seg_start int32[T], pos int32[T]) for the packed sequence [chunks, tail]."""
+    lens, lens_p = _host(chunk_lens, np.int32)
+    total = int(lens.sum()) + int(n_tail)
+    seg = np.zeros(max(total, 1), np.int32)
+    pos = np.zeros(max(total, 1), np.int32)
+    _check(lib().tr_sequence_plan(lens_p, C.c_int32(lens.size), C.c_int32(n_tail), C.c_int32(pos_mode), C.c_int32(tail_start),
+                                  seg.ctypes.data_as(C.c_void_p), pos.ctypes.data_as(C.c_void_p), C.c_int64(total)))
+    return seg[:total], pos[:total]
+
+
+def tr_sequence_prefill_attn(shape, q, k, v, seg_start, pos, out, k_rot_out, stream=None):
+    _check(lib().tr_sequence_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(seg_start), _dev(pos),
+                                          C.c_int64(q.shape[0]), _dev(out), _dev(k_rot_out), _stream(stream)))
 
 
 def workspace(nbytes, device="cuda"):

@@ -704,6 +704,82 @@ extern "C" int tr_prefill_attn_gather(const tr_store* store, const int32_t* chun
     return tr_launch_gather_attn(a, ca, sh->head_dim, (hipStream_t)stream);
 }
 
+// ---- one pass over a packed sequence with per-token visible ranges and position ids -----------------------------
+extern "C" int tr_sequence_plan(const int32_t* chunk_lens, int32_t n_chunks, int32_t n_tail, int32_t pos_mode, int32_t tail_start,
+                                int32_t* seg_start, int32_t* pos, int64_t capacity)
+{
+    tr_clear_error();
+    if (n_chunks < 0 || n_tail < 0) return tr_fail(TR_ERR_INVALID_ARG, "negative count");
+    if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
+    if (n_chunks > 0 && !chunk_lens) return tr_fail(TR_ERR_INVALID_ARG, "chunk_lens is NULL");
+    int64_t n_doc = 0, longest = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (chunk_lens[c] < 0) return tr_fail(TR_ERR_INVALID_ARG, "chunk_lens[%d] < 0", c);
+        n_doc += chunk_lens[c];
+        longest = std::max<int64_t>(longest, chunk_lens[c]);
+    }
+    const int64_t total = n_doc + n_tail;
+    if (total > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "2^31 tokens or more");
+    if (total > capacity) return tr_fail(TR_ERR_BAD_PLAN, "the sequence has %lld tokens, the arrays hold %lld", (long long)total, (long long)capacity);
+    if (total > 0 && (!seg_start || !pos)) return tr_fail(TR_ERR_INVALID_ARG, "seg_start or pos is NULL");
+    int64_t off = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        for (int64_t t = 0; t < chunk_lens[c]; ++t) {
+            seg_start[off + t] = (int32_t)off;
+            pos[off + t] = (int32_t)(pos_mode == TR_POS_REORDERED ? off + t : t);
+        }
+        off += chunk_lens[c];
+    }
+    const int64_t start = tail_start >= 0 ? tail_start : (pos_mode == TR_POS_REORDERED ? n_doc : longest);
+    for (int64_t i = 0; i < n_tail; ++i) {
+        seg_start[n_doc + i] = 0;
+        pos[n_doc + i] = (int32_t)(start + i);
+    }
+    return TR_OK;
+}
+
+extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* seg_start,
+                                        const int32_t* pos, int64_t total_tokens, void* out, void* k_rot_out, void* stream)
+{
+    tr_clear_error();
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    if (total_tokens < 0) return tr_fail(TR_ERR_INVALID_ARG, "total_tokens < 0");
+    if (total_tokens > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "2^31 tokens or more");
+    if (total_tokens == 0) return TR_OK;
+    if (!q || !k || !v || !seg_start || !pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_sequence_prefill_attn: NULL pointer");
+    if (!k_rot_out) return tr_fail(TR_ERR_INVALID_ARG, "k_rot_out is required (it may alias k)");
+    hipStream_t s = (hipStream_t)stream;
+    // keys rotated at their position ids, fp64, one rounding (the arithmetic of the query append), values untouched
+    std::vector<TrAppendDesc> d(1);
+    d[0].q_row0 = 0;
+    d[0].n_q = (int32_t)total_tokens;
+    d[0].dst_row0 = 0;
+    rc = launch_append(shape, k, nullptr, pos, d, k_rot_out, nullptr, s);
+    if (rc) return rc;
+    TrBlockDiagArgs a;
+    memset(&a, 0, sizeof a);
+    tr_fill_theta(shape, a.theta);
+    for (int m = 0; m < 64; ++m) a.theta_rev[m] = a.theta[m] / 6.283185307179586476925;
+    a.q = q;
+    a.k = k_rot_out;
+    a.v = v;
+    a.tok_start = seg_start;
+    a.pos = pos;
+    a.out = out;
+    a.total_tokens = (int32_t)total_tokens;
+    a.n_q_heads = shape->n_q_heads;
+    a.n_kv_heads = shape->n_kv_heads;
+    a.group = shape->n_q_heads / shape->n_kv_heads;
+    const int wg_rows = env_int("TR_WG_ROWS", 0) == 256 ? 256 : 128;
+    a.tok_per_tile = wg_rows / a.group;
+    a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);
+    a.scale = (float)(1.0 / sqrt((double)shape->head_dim));
+    a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)shape->head_dim));
+    if (shape->dtype == TR_F32) return tr_launch_blockdiag_attn_f32(a, shape->head_dim, s);
+    return tr_launch_blockdiag_attn(a, shape->head_dim, wg_rows, s);
+}
+
 // ---- decode step: one query token per request ---------------------------------------------------------------------
 namespace {
 int decode_cu(int32_t n_req, std::vector<int32_t>* cu)

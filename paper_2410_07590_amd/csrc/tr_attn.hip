@@ -978,7 +978,9 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     LDS_AS char* smem = (LDS_AS char*)smem_raw;
     const int n_items = a.n_tiles * a.n_kv_heads;
     const int item = xcd_remap(blockIdx.x, n_items);
-    const int tile = item % a.n_tiles;
+    // last row tiles first: under a causal mask they walk the most keys (a query behind the documents walks all of
+    // them), so they must not be the ones that start last
+    const int tile = a.n_tiles - 1 - item % a.n_tiles;
     const int kvh = item / a.n_tiles;
     const int g = a.group, tpt = a.tok_per_tile;
     const int T = a.total_tokens;
@@ -992,17 +994,28 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     rc.orow = t * a.n_q_heads + kvh * g + rl % g;
     rc.key_lo = rc.valid ? chunk_start(a.tok_start, t) : 0;
     rc.key_hi = t;
-    // chunk-local position of each token slot of this wave
+    // position id of each token slot of this wave: given, or chunk-local
     const int wave_t0 = tile * tpt + (32 * wave) / g;
-    auto pos_of_slot = [&](int s) { const int ts = min(wave_t0 + s, T - 1); return ts - chunk_start(a.tok_start, ts); };
+    auto pos_of_slot = [&](int s) {
+        const int ts = min(wave_t0 + s, T - 1);
+        return a.pos ? a.pos[ts] : ts - chunk_start(a.tok_start, ts);
+    };
     const int pos_lane = pos_of_slot(lane & (ROT_SLOTS - 1));
     const int slot = min(rl / g - (32 * wave) / g, 31);
     const int n_slots = (32 * wave + 31) / g - (32 * wave) / g + 1;
 
+    // first row any token of the tile attends, and the largest such start (tiles below it need the lower mask);
+    // the starts need not be monotone: a query token behind the documents starts at row 0 again
     const int t_first = tile * tpt;
     const int t_last = min(t_first + tpt, T) - 1;
-    const int lo_first = chunk_start(a.tok_start, t_first);
-    const int lo_last = chunk_start(a.tok_start, t_last);
+    int lo_first = INT32_MAX, lo_last = 0;
+    for (int tt = t_first + lane; tt <= t_last; tt += 64) {
+        const int st = chunk_start(a.tok_start, tt);
+        lo_first = min(lo_first, st);
+        lo_last = max(lo_last, st);
+    }
+    lo_first = wave_min_i(lo_first);
+    lo_last = wave_max_i(lo_last);
     const Walk w = make_walk(lo_first, t_last + 1, T - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];

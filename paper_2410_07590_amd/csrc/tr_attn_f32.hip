@@ -119,10 +119,10 @@ __global__ __launch_bounds__(64) void blockdiag_attn_f32_kernel(const TrBlockDia
     F32Row r;
     r.q = (const float*)a.q + ((int64_t)t * a.n_q_heads + hq) * D;
     r.out = (float*)a.out + ((int64_t)t * a.n_q_heads + hq) * D;
-    r.key_lo = a.tok_start[t];
+    r.key_lo = min(max(a.tok_start[t], 0), t);
     r.key_hi = t;
     r.kvh = hq / a.group;
-    r.pos = (double)(t - r.key_lo);
+    r.pos = a.pos ? (double)a.pos[t] : (double)(t - r.key_lo);
     attn_f32_row<D>(r, (const float*)a.k, (const float*)a.v, a.n_kv_heads, a.theta, a.scale);
 }
 

@@ -96,7 +96,10 @@ __device__ __forceinline__ void append_pair(const void* k_new, const void* v_new
         Pair kx[APPEND_MAX_HEADS], vx[APPEND_MAX_HEADS];
 #pragma unroll
         for (int j = 0; j < APPEND_MAX_HEADS; ++j)
-            if (h0 + j < n_kv_heads) { kx[j] = ks[(h0 + j) * half]; vx[j] = vs[(h0 + j) * half]; }
+            if (h0 + j < n_kv_heads) {
+                kx[j] = ks[(h0 + j) * half];
+                if (v_new) vx[j] = vs[(h0 + j) * half];
+            }
         if (h0 == 0) sincos(angle, &sn, &cn);
 #pragma unroll
         for (int j = 0; j < APPEND_MAX_HEADS; ++j)
@@ -112,7 +115,7 @@ __device__ __forceinline__ void append_pair(const void* k_new, const void* v_new
                 rotate_pair(xa, xb, cn, sn, ya, yb);
                 if constexpr (DTYPE == TR_BF16) kd[(h0 + j) * half] = double_to_bf16_bits(ya) | (double_to_bf16_bits(yb) << 16);
                 else kd[(h0 + j) * half] = make_float2(__double2float_rn(ya), __double2float_rn(yb));
-                vd[(h0 + j) * half] = vx[j];
+                if (v_new) vd[(h0 + j) * half] = vx[j]; // v_new == NULL: keys only
             }
     }
 }

@@ -167,7 +167,8 @@ struct TrBlockDiagArgs {
     const void* q;
     const void* k; // rotated keys K'
     const void* v;
-    const int32_t* tok_start; // [T] first row of the chunk that owns each token
+    const int32_t* tok_start; // [T] first row each token may attend (the start of its chunk)
+    const int32_t* pos;       // [T] RoPE position ids, or NULL: position = t - tok_start[t]
     void* out;
     int32_t total_tokens;
     int32_t n_tiles;

@@ -283,3 +283,32 @@ def test_binding_raises_with_the_library_message(L):
     with pytest.raises(B.TurboRagError) as e:
         B.Store(sh, None, None, np.array([0, 4]))
     assert e.value.code in (B.TR_ERR_SHAPE, B.TR_ERR_INVALID_ARG)
+
+
+@pytest.mark.parametrize("mode", [B.TR_POS_COMPOSITE, B.TR_POS_REORDERED])
+def test_sequence_plan_is_bit_exact_against_the_oracle(L, mode):
+    for lens, n_tail, tail_start in [((3, 2), 2, -1), ((512,) * 8, 64, -1), ((), 5, -1), ((7, 0, 9), 0, -1), ((4, 4), 3, 100)]:
+        seg, pos = B.tr_sequence_plan(lens, n_tail, mode, tail_start)
+        want_seg, want_pos = oracle.sequence_plan(lens, n_tail, mode, None if tail_start < 0 else tail_start)
+        assert np.array_equal(seg, want_seg) and np.array_equal(pos, want_pos)
+    lens, lens_p = _i32([3, 2])
+    buf = np.zeros(8, np.int32)
+    bp = buf.ctypes.data_as(C.c_void_p)
+    assert L.tr_sequence_plan(lens_p, C.c_int32(2), C.c_int32(2), C.c_int32(mode), C.c_int32(-1), bp, bp, C.c_int64(6)) == B.TR_ERR_BAD_PLAN
+    assert L.tr_sequence_plan(lens_p, C.c_int32(2), C.c_int32(2), C.c_int32(7), C.c_int32(-1), bp, bp, C.c_int64(8)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_sequence_plan(None, C.c_int32(2), C.c_int32(2), C.c_int32(mode), C.c_int32(-1), bp, bp, C.c_int64(8)) == B.TR_ERR_INVALID_ARG
+    bad, bad_p = _i32([3, -2])
+    assert L.tr_sequence_plan(bad_p, C.c_int32(2), C.c_int32(2), C.c_int32(mode), C.c_int32(-1), bp, bp, C.c_int64(8)) == B.TR_ERR_INVALID_ARG
+
+
+def test_sequence_prefill_validation(L):
+    sh = _shape()
+    call = lambda **kw: L.tr_sequence_prefill_attn(C.byref(kw.get("shape", sh)), kw.get("q", FAKE), FAKE, FAKE, kw.get("seg", FAKE),
+                                                   kw.get("pos", FAKE), C.c_int64(kw.get("T", 100)), FAKE, kw.get("krot", FAKE2), None)
+    assert call(q=None) == B.TR_ERR_INVALID_ARG
+    assert call(seg=None) == B.TR_ERR_INVALID_ARG
+    assert call(pos=None) == B.TR_ERR_INVALID_ARG
+    assert call(krot=None) == B.TR_ERR_INVALID_ARG
+    assert call(T=-1) == B.TR_ERR_INVALID_ARG
+    assert call(shape=_shape(d=96)) == B.TR_ERR_SHAPE
+    assert call(T=0) == B.TR_OK

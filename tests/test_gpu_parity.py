@@ -430,3 +430,70 @@ def test_offline_store_feeds_online_path(B):
                               oracle.widen(raw_v))
     err = float(np.abs(H.to_f64(g["out"]) - want).max())
     assert err <= H.BF16_TOL, err
+
+
+# ---- one pass over [chunks, query/answer] with the masks and position ids of inference (Sec. 3.3) ---------------
+def _run_sequence(B, sh, q, k, v, seg, pos):
+    gs = H.gpu_shape(B, sh)
+    out = torch.full(q.shape, float("nan"), dtype=sh.torch_dtype, device="cuda")
+    k_rot = torch.full(k.shape, float("nan"), dtype=sh.torch_dtype, device="cuda")
+    B.tr_sequence_prefill_attn(gs, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(seg).cuda(), torch.from_numpy(pos).cuda(), out, k_rot)
+    torch.cuda.synchronize()
+    return out.cpu(), k_rot.cpu()
+
+
+def _check_sequence(B, sh, lens, n_tail, mode, seed, rows=None):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    seg, pos = B.tr_sequence_plan(lens, n_tail, mode)
+    want_seg, want_pos = oracle.sequence_plan(lens, n_tail, mode)
+    assert np.array_equal(seg, want_seg) and np.array_equal(pos, want_pos)
+    T = seg.size
+    q = synth.normal_tensor(rng, (T, sh.n_q_heads, sh.head_dim), sh.torch_dtype)
+    k = synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype)
+    v = synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype)
+    out, k_rot = _run_sequence(B, sh, q, k, v, seg, pos)
+    o = oracle.masked_prefill(H.bits(q), H.bits(k), H.bits(v), want_seg, want_pos, sh.rope_base, rows=rows)
+    H.assert_same_bits(H.bits(k_rot), o["k_rot_st"], "keys rotated at their position ids", 1e-5)
+    got = H.to_f64(out)
+    if rows is not None:
+        got = got[np.asarray(rows)]
+    assert np.isfinite(got).all()
+    err = float(np.abs(got - o["out"]).max())
+    assert err <= H.tol_for(sh), "one-pass attention max abs err %.3e" % err
+    return err
+
+
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+def test_sequence_one_pass_ragged(B, mode):
+    worst = 0.0
+    for i, (sh, lens, n_tail) in enumerate([(synth.QWEN2_7B, (70, 1, 129, 33, 64), 37), (synth.LLAMA3_8B, (200, 5), 130),
+                                            (synth.Shape(8, 8, 64, "bf16", 1e4), (40, 90), 20),
+                                            (synth.Shape(4, 4, 64, "f32", 1e4), (64, 64), 16),
+                                            (synth.QWEN2_7B, (), 50), (synth.QWEN2_7B, (100, 60), 0)]):
+        worst = max(worst, _check_sequence(B, sh, lens, n_tail, mode, 300 + i))
+    print("one-pass sequence attention, mode %d: max abs err %.3e" % (mode, worst))
+
+
+def test_sequence_one_pass_config2_shape_sampled(B):
+    """[8 chunks x 512, 64 query tokens] at the Qwen2-7B shape: the fine-tuning / whole-prefill form of configuration 2."""
+    T = 8 * 512 + 64
+    rows = np.unique(np.concatenate([np.arange(0, T, 257), np.arange(T - 64, T, 9), [511, 512, T - 1]])).astype(np.int32)
+    err = _check_sequence(B, synth.QWEN2_7B, (512,) * 8, 64, synth.POS_REORDERED, 310, rows)
+    print("one-pass sequence, 8 x 512 + 64: max abs err %.3e on %d sampled tokens" % (err, rows.size))
+
+
+def test_sequence_form_reproduces_the_offline_chunk_prefill(B):
+    """Chunk starts and chunk-local ids through the general entry point: same bytes as tr_chunk_prefill_attn."""
+    sh = synth.LLAMA3_8B
+    lens = (70, 1, 129, 33, 64, 200, 5)
+    rng = np.random.Generator(np.random.PCG64(311))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    pc = synth.PackedChunks(synth.normal_tensor(rng, (T, sh.n_q_heads, sh.head_dim), sh.torch_dtype),
+                            synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype),
+                            synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype), cu)
+    out_a, krot_a = _run_offline(B, sh, pc)
+    seg, pos = B.tr_sequence_plan(lens, 0, synth.POS_COMPOSITE)
+    out_b, krot_b = _run_sequence(B, sh, pc.q, pc.k, pc.v, seg, pos)
+    assert np.array_equal(H.bits(krot_a), H.bits(krot_b))
+    assert np.array_equal(H.bits(out_a), H.bits(out_b))
