@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 N_VARIANTS = 16
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters read
-# on a copy kernel of known size (see profiles/ and the design doc).  None where not measured.
+# on a copy kernel of known size (the summaries are under profiles/).  None where not measured.
 MEASURED_TRAFFIC = {
     ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 23825433,       # prefix_attn 16.5 MB (6.2 MB of split partials written) + combine 7.3 MB
     ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16954640,
