@@ -609,6 +609,7 @@ int plan_gather(const tr_store* store, const int32_t* chunk_ids, const int64_t* 
     p->tok_per_tile = 128 / g;
     p->row_tiles = (n_q + p->tok_per_tile - 1) / p->tok_per_tile;
     const int base_items = p->row_tiles * sh->n_kv_heads;
+    if (base_items == 0) return TR_OK; // no query tokens: nothing will be launched
     int want = base_items < TARGET_ITEMS ? (TARGET_ITEMS + base_items - 1) / base_items : 1;
     if (want > MAX_SPLIT) want = MAX_SPLIT;
     const int max_split = std::max(1, tiles / (MIN_SPLIT_KEYS / KEY_TILE));

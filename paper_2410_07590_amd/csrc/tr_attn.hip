@@ -928,12 +928,13 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
     for (int e = 0; e < CPLN; ++e) acc[e] = 0.0f;
     const _Float16* base = a.ws_o + prow0 * D + CPLN * lane_r;
     const int row_lane0 = threadIdx.x & 32; // first lane of this row's half-wave
-    // four splits per round so that four loads are in flight (the loop count is a run-time value)
-    for (int sp0 = 0; sp0 < sd.n_split; sp0 += 4) {
-        f32x4 x[4];
-        float w[4];
+    // eight splits per round so that eight loads are in flight (the loop count is a run-time value)
+    constexpr int PER_ROUND = 8;
+    for (int sp0 = 0; sp0 < sd.n_split; sp0 += PER_ROUND) {
+        f32x4 x[PER_ROUND];
+        float w[PER_ROUND];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < PER_ROUND; ++u) {
             const int sp = sp0 + u;
             const bool ok = sp < sd.n_split;
             const _Float16* p = base + (int64_t)(ok ? sp : 0) * pstride * D;
@@ -949,7 +950,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
             w[u] = ok ? ws : 0.0f;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < PER_ROUND; ++u)
 #pragma unroll
             for (int e = 0; e < CPLN; ++e) acc[e] += w[u] * x[u][e];
     }

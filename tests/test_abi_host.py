@@ -312,3 +312,60 @@ def test_sequence_prefill_validation(L):
     assert call(T=-1) == B.TR_ERR_INVALID_ARG
     assert call(shape=_shape(d=96)) == B.TR_ERR_SHAPE
     assert call(T=0) == B.TR_OK
+
+
+def test_gather_attention_validation(L):
+    rc, h = _store(L, _shape(), [0, 4, 9, 9, 20])
+    assert rc == B.TR_OK
+    ids, ids_p = _i32([1, 3, 0])
+    good, good_p = _i64([0, 5, 16, 20])
+    size = L.tr_prefill_attn_gather_workspace_size(h, ids_p, good_p, C.c_int32(3), C.c_int32(1), C.c_int32(8))
+    assert size == 0          # 20 document rows: nothing to split
+
+    def call(ids_p=ids_p, off_p=good_p, n=3, mode=B.TR_POS_REORDERED, q=FAKE, ck=FAKE, n_q=8, cap=28, store=h):
+        return L.tr_prefill_attn_gather(store, ids_p, off_p, C.c_int32(n), C.c_int32(mode), q, ck, FAKE2, FAKE, C.c_int32(n_q),
+                                        C.c_int64(cap), FAKE2, None, C.c_size_t(0), None)
+
+    bad, bad_p = _i64([0, 5, 15, 20])
+    assert call(off_p=bad_p) == B.TR_ERR_BAD_PLAN
+    badid, badid_p = _i32([1, 9, 0])
+    assert call(ids_p=badid_p) == B.TR_ERR_BAD_CHUNK_ID
+    assert call(cap=27) == B.TR_ERR_BAD_PLAN                  # the query rows do not fit the cache
+    assert call(q=None) == B.TR_ERR_INVALID_ARG
+    assert call(ck=None) == B.TR_ERR_INVALID_ARG
+    assert call(store=None) == B.TR_ERR_INVALID_ARG
+    assert call(mode=3) == B.TR_ERR_INVALID_ARG
+    assert call(n_q=-1) == B.TR_ERR_INVALID_ARG
+    assert call(n_q=0) == B.TR_OK
+    L.tr_store_destroy(h)
+    rc, h32 = _store(L, _shape(4, 4, 64, B.TR_F32, 1e4), [0, 4])
+    one, one_p = _i32([0])
+    off, off_p = _i64([0, 4])
+    assert call(store=h32, ids_p=one_p, off_p=off_p, n=1) == B.TR_ERR_UNSUPPORTED     # bf16 only
+    L.tr_store_destroy(h32)
+
+
+def test_assemble_append_and_decode_validation(L):
+    rc, h = _store(L, _shape(), [0, 4, 9, 9, 20])
+    ids, ids_p = _i32([1, 3, 0])
+    good, good_p = _i64([0, 5, 16, 20])
+
+    def fused(n_q=4, cap=24, k=FAKE, off_p=good_p):
+        return L.tr_kv_assemble_append(h, ids_p, off_p, C.c_int32(3), C.c_int32(1), k, FAKE, FAKE, C.c_int32(n_q), FAKE2, FAKE2,
+                                       C.c_int64(cap), None)
+
+    assert fused(cap=23) == B.TR_ERR_BAD_PLAN                 # documents fit, the query rows do not
+    assert fused(k=None) == B.TR_ERR_INVALID_ARG
+    assert fused(n_q=-1) == B.TR_ERR_INVALID_ARG
+    bad, bad_p = _i64([0, 5, 15, 20])
+    assert fused(off_p=bad_p) == B.TR_ERR_BAD_PLAN
+    L.tr_store_destroy(h)
+
+    sh = _shape()
+    rows, rows_p = _i64([0, 100, 100, 250])                    # the second request has no cache row at all
+    assert L.tr_decode_attn(C.byref(sh), FAKE, FAKE, FAKE, FAKE, rows_p, C.c_int32(3), FAKE, None, C.c_size_t(0), None) == B.TR_ERR_INVALID_ARG
+    ok, ok_p = _i64([0, 100, 180, 250])
+    assert L.tr_decode_attn_workspace_size(C.byref(sh), ok_p, C.c_int32(3)) == 0      # short caches: no key split
+    assert L.tr_decode_attn(C.byref(sh), None, FAKE, FAKE, FAKE, ok_p, C.c_int32(3), FAKE, None, C.c_size_t(0), None) == B.TR_ERR_INVALID_ARG
+    assert L.tr_decode_attn(C.byref(sh), FAKE, FAKE, FAKE, FAKE, ok_p, C.c_int32(-1), FAKE, None, C.c_size_t(0), None) == B.TR_ERR_INVALID_ARG
+    assert L.tr_decode_attn(C.byref(sh), FAKE, FAKE, FAKE, FAKE, ok_p, C.c_int32(0), FAKE, None, C.c_size_t(0), None) == B.TR_OK

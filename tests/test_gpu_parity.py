@@ -276,7 +276,7 @@ def test_gather_attention_without_documents_and_composite_batch(B):
 
 # ---- decode step (Sec. 3.4 step 7): one new token per request over its assembled cache ---------------------------
 DECODE_SHAPES = [synth.QWEN2_7B, synth.LLAMA3_8B, synth.Shape(14, 2, 64, "bf16", 1.0e6), synth.Shape(8, 8, 64, "bf16", 1.0e4),
-                 synth.Shape(32, 1, 128, "bf16", 5.0e5)]
+                 synth.Shape(32, 1, 128, "bf16", 5.0e5), synth.Shape(40, 20, 128, "bf16", 1.0e4)]   # the last: 20 KV heads
 
 
 @pytest.mark.parametrize("shape_no", range(len(DECODE_SHAPES)))
