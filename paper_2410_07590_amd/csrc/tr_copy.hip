@@ -13,9 +13,11 @@ __device__ __forceinline__ double bf16_bits_to_double(uint32_t b16)
     return (double)__uint_as_float(b16 << 16);
 }
 
-// double -> bf16 with a single rounding (nearest, ties to even): truncate to fp32, fold the discarded
-// bits into a sticky last bit (round to odd), then round the 24-bit significand to 8 bits.
-__device__ __forceinline__ uint32_t double_to_bf16_bits(double y)
+// double -> bf16 with a single rounding (nearest, ties to even), done on the bit pattern: the 45 mantissa bits
+// below bf16's seven are folded to "above / at / below half" with integer arithmetic (the low word only matters as
+// a sticky bit), and a carry out of the mantissa lands in the exponent as it should.  Values outside bf16's normal
+// range (zero, subnormal, overflow, NaN) take the conversion route: truncate to fp32, sticky bit, round.
+__device__ __forceinline__ uint32_t double_to_bf16_bits_slow(double y)
 {
     float f = __double2float_rz(y);
     uint32_t u = __float_as_uint(f);
@@ -23,6 +25,17 @@ __device__ __forceinline__ uint32_t double_to_bf16_bits(double y)
     if (y != y) return 0x7fc0u;
     u += 0x7fffu + ((u >> 16) & 1u);
     return u >> 16;
+}
+__device__ __forceinline__ uint32_t double_to_bf16_bits(double y)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(y);
+    uint32_t hi = (uint32_t)(b >> 32);
+    hi |= ((uint32_t)b != 0u) ? 1u : 0u;          // sticky: bit 0 is among the 13 bits rounded away
+    hi += 0xfffu + ((hi >> 13) & 1u);             // nearest, ties to even, at bit 13
+    const uint32_t t = hi >> 13;                  // sign | 11-bit exponent | 7-bit mantissa
+    const uint32_t e = ((t >> 7) & 0x7ffu) - 896u; // exponent rebased from 1023 to 127
+    if (e - 1u < 254u) return ((t >> 18) << 15) | (e << 7) | (t & 0x7fu);
+    return double_to_bf16_bits_slow(y);
 }
 
 // y = R(angle) x on one pair, unfused multiplies and adds (the order Eq. 3 is written in)
