@@ -44,7 +44,8 @@ typedef enum {
     TR_ERR_SHAPE = -4,        /* unsupported head_dim / head counts / dtype */
     TR_ERR_UNSUPPORTED = -5,  /* valid request the library does not implement */
     TR_ERR_HIP = -6,          /* a HIP runtime call failed (message holds hipGetErrorString) */
-    TR_ERR_WORKSPACE = -7     /* workspace missing, misaligned or too small */
+    TR_ERR_WORKSPACE = -7,    /* workspace missing, misaligned or too small */
+    TR_ERR_NO_MEMORY = -8     /* host memory for the call's bookkeeping could not be allocated */
 } tr_status;
 
 typedef enum { TR_POS_COMPOSITE = 0, TR_POS_REORDERED = 1 } tr_pos_mode; /* Sec. 3.2 */

@@ -14,7 +14,7 @@ from . import build as _build
 
 TR_OK = 0
 TR_ERR_INVALID_ARG, TR_ERR_BAD_CHUNK_ID, TR_ERR_BAD_PLAN, TR_ERR_SHAPE = -1, -2, -3, -4
-TR_ERR_UNSUPPORTED, TR_ERR_HIP, TR_ERR_WORKSPACE = -5, -6, -7
+TR_ERR_UNSUPPORTED, TR_ERR_HIP, TR_ERR_WORKSPACE, TR_ERR_NO_MEMORY = -5, -6, -7, -8
 TR_POS_COMPOSITE, TR_POS_REORDERED = 0, 1
 TR_F32, TR_BF16 = 0, 1
 TR_ROPE_INTERLEAVED, TR_ROPE_HALF = 0, 1

@@ -24,6 +24,26 @@ void tr_clear_error() { g_err[0] = 0; }
 
 extern "C" const char* tr_last_error(void) { return g_err; }
 
+// No C++ exception may cross the C boundary: the entry points run inside these.
+template <class F> static int tr_guard_int(F&& f)
+{
+    try {
+        return f();
+    } catch (const std::bad_alloc&) {
+        return tr_fail(TR_ERR_NO_MEMORY, "out of host memory");
+    } catch (...) {
+        return tr_fail(TR_ERR_INVALID_ARG, "unexpected C++ exception");
+    }
+}
+template <class F> static size_t tr_guard_size(F&& f)
+{
+    try {
+        return f();
+    } catch (...) {
+        return 0;
+    }
+}
+
 int tr_check_shape(const tr_shape* s)
 {
     if (!s) return tr_fail(TR_ERR_INVALID_ARG, "shape is NULL");
@@ -51,6 +71,7 @@ static const int64_t ROW_LIMIT = ((int64_t)1 << 31) - 1;
 extern "C" int tr_store_create(const tr_shape* shape, const void* k_store, const void* v_store,
                                const int64_t* chunk_row_start, int32_t n_chunks, tr_store** out)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     if (!out) return tr_fail(TR_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
@@ -63,26 +84,30 @@ extern "C" int tr_store_create(const tr_shape* shape, const void* k_store, const
     if (chunk_row_start[n_chunks] > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "store has 2^31 rows or more");
     if (chunk_row_start[n_chunks] > 0 && (!k_store || !v_store)) return tr_fail(TR_ERR_INVALID_ARG, "store pointer is NULL");
     tr_store* st = new (std::nothrow) tr_store;
-    if (!st) return tr_fail(TR_ERR_INVALID_ARG, "out of host memory");
+    if (!st) return tr_fail(TR_ERR_NO_MEMORY, "out of host memory");
     st->shape = *shape;
     st->k = k_store;
     st->v = v_store;
     st->row_start.assign(chunk_row_start, chunk_row_start + n_chunks + 1);
     *out = st;
     return TR_OK;
+    });
 }
 
 extern "C" int tr_store_destroy(tr_store* store)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     delete store;
     return TR_OK;
+    });
 }
 
 // ---- plan (Sec. 3.2) --------------------------------------------------------------------------------------------
 extern "C" int tr_plan(const tr_store* store, const int32_t* chunk_ids, int32_t n, int32_t pos_mode,
                        int64_t* offsets, int32_t* pos_ids, int64_t pos_capacity)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     if (!store || !offsets || n < 0 || (n > 0 && !chunk_ids)) return tr_fail(TR_ERR_INVALID_ARG, "tr_plan: NULL argument or n < 0");
     if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
@@ -105,6 +130,7 @@ extern "C" int tr_plan(const tr_store* store, const int32_t* chunk_ids, int32_t 
         }
     }
     return TR_OK;
+    });
 }
 
 // ---- KV-cache formation ---------------------------------------------------------------------------------------------
@@ -173,6 +199,7 @@ int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* o
 extern "C" int tr_kv_assemble(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
                               int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     if (!store || n_chunks < 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble: store NULL or n_chunks < 0");
     if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
@@ -195,12 +222,14 @@ extern "C" int tr_kv_assemble(const tr_store* store, const int32_t* chunk_ids, c
     if (off > out_capacity_rows) return tr_fail(TR_ERR_BAD_PLAN, "plan needs %lld rows, the cache holds %lld", (long long)off, (long long)out_capacity_rows);
     if (off > 0 && (!out_k || !out_v)) return tr_fail(TR_ERR_INVALID_ARG, "out_k or out_v is NULL");
     return launch_runs(store, runs, out_k, out_v, (hipStream_t)stream);
+    });
 }
 
 extern "C" int tr_kv_assemble_batched(const tr_store* store, const int32_t* chunk_ids, const int32_t* cu_chunks,
                                       const int32_t* pos_modes, const int64_t* cache_row_start, int32_t n_req,
                                       void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     if (!store || n_req < 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble_batched: store NULL or n_req < 0");
     if (n_req == 0) return TR_OK;
@@ -231,6 +260,7 @@ extern "C" int tr_kv_assemble_batched(const tr_store* store, const int32_t* chun
     if (cache_row_start[n_req] > out_capacity_rows) return tr_fail(TR_ERR_BAD_PLAN, "cache ranges end at row %lld, the cache holds %lld", (long long)cache_row_start[n_req], (long long)out_capacity_rows);
     if (total > 0 && (!out_k || !out_v)) return tr_fail(TR_ERR_INVALID_ARG, "out_k or out_v is NULL");
     return launch_runs(store, runs, out_k, out_v, (hipStream_t)stream);
+    });
 }
 
 // ---- query append ---------------------------------------------------------------------------------------------------
@@ -268,6 +298,7 @@ int launch_append(const tr_shape* shape, const void* k_new, const void* v_new, c
 extern "C" int tr_kv_append(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos, int32_t n_q,
                             void* cache_k, void* cache_v, int64_t dst_row, int64_t cache_capacity_rows, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     int rc = tr_check_shape(shape);
     if (rc) return rc;
@@ -281,6 +312,7 @@ extern "C" int tr_kv_append(const tr_shape* shape, const void* k_new, const void
     d[0].n_q = n_q;
     d[0].dst_row0 = (int32_t)dst_row;
     return launch_append(shape, k_new, v_new, q_pos, d, cache_k, cache_v, (hipStream_t)stream);
+    });
 }
 
 // assemble + append of one request in a single launch
@@ -288,6 +320,7 @@ extern "C" int tr_kv_assemble_append(const tr_store* store, const int32_t* chunk
                                      int32_t pos_mode, const void* k_new, const void* v_new, const int32_t* q_pos, int32_t n_q,
                                      void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     if (!store) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble_append: store is NULL");
     if (n_q < 0 || n_chunks < 0) return tr_fail(TR_ERR_INVALID_ARG, "negative count");
@@ -327,12 +360,14 @@ extern "C" int tr_kv_assemble_append(const tr_store* store, const int32_t* chunk
     tail.first_block = 0;
     tail.n_kv_heads = store->shape.n_kv_heads;
     return launch_runs(store, runs, out_k, out_v, (hipStream_t)stream, &tail);
+    });
 }
 
 extern "C" int tr_kv_append_batched(const tr_shape* shape, const void* k_new, const void* v_new, const int32_t* q_pos,
                                     const int32_t* cu_q, const int64_t* cache_row_start, int32_t n_req, void* cache_k,
                                     void* cache_v, int64_t cache_capacity_rows, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     int rc = tr_check_shape(shape);
     if (rc) return rc;
@@ -356,6 +391,7 @@ extern "C" int tr_kv_append_batched(const tr_shape* shape, const void* k_new, co
     }
     if (cu_q[n_req] > 0 && (!k_new || !v_new || !q_pos || !cache_k || !cache_v)) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_append_batched: NULL pointer");
     return launch_append(shape, k_new, v_new, q_pos, d, cache_k, cache_v, (hipStream_t)stream);
+    });
 }
 
 // ---- query prefill attention ------------------------------------------------------------------------------------------
@@ -509,14 +545,17 @@ int batched_geom(const int32_t* cu_q, const int64_t* cache_row_start, int32_t n_
 
 extern "C" size_t tr_prefill_attn_workspace_size(const tr_shape* shape, int32_t n_q, int64_t kv_len)
 {
+    return tr_guard_size([&]() -> size_t {
     if (tr_check_shape(shape) || n_q <= 0 || kv_len < n_q || kv_len > ROW_LIMIT) return 0;
     std::vector<ReqGeom> reqs{{0, n_q, 0, kv_len}};
     return prefix_ws_bytes(shape, reqs);
+    });
 }
 
 extern "C" int tr_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* q_pos,
                                int32_t n_q, int64_t kv_len, void* out, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     int rc = tr_check_shape(shape);
     if (rc) return rc;
@@ -527,20 +566,24 @@ extern "C" int tr_prefill_attn(const tr_shape* shape, const void* q, const void*
     if (!q || !k || !v || !q_pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn: NULL pointer");
     std::vector<ReqGeom> reqs{{0, n_q, 0, kv_len}};
     return run_prefix(shape, q, k, v, q_pos, reqs, out, workspace, workspace_bytes, (hipStream_t)stream);
+    });
 }
 
 extern "C" size_t tr_prefill_attn_batched_workspace_size(const tr_shape* shape, const int32_t* cu_q,
                                                          const int64_t* cache_row_start, int32_t n_req)
 {
+    return tr_guard_size([&]() -> size_t {
     std::vector<ReqGeom> reqs;
     if (tr_check_shape(shape) || batched_geom(cu_q, cache_row_start, n_req, &reqs)) return 0;
     return prefix_ws_bytes(shape, reqs);
+    });
 }
 
 extern "C" int tr_prefill_attn_batched(const tr_shape* shape, const void* q, const void* k, const void* v,
                                        const int32_t* q_pos, const int32_t* cu_q, const int64_t* cache_row_start,
                                        int32_t n_req, void* out, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     int rc = tr_check_shape(shape);
     if (rc) return rc;
@@ -550,6 +593,7 @@ extern "C" int tr_prefill_attn_batched(const tr_shape* shape, const void* q, con
     if (n_req == 0 || cu_q[n_req] == 0) return TR_OK;
     if (!q || !k || !v || !q_pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn_batched: NULL pointer");
     return run_prefix(shape, q, k, v, q_pos, reqs, out, workspace, workspace_bytes, (hipStream_t)stream);
+    });
 }
 
 // ---- query prefill that gathers the chunks itself (no assembled document rows needed) ---------------------------
@@ -631,10 +675,12 @@ size_t gather_ws_bytes(const tr_shape* sh, const GatherPlan& p, int32_t n_q)
 extern "C" size_t tr_prefill_attn_gather_workspace_size(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets,
                                                         int32_t n_chunks, int32_t pos_mode, int32_t n_q)
 {
+    return tr_guard_size([&]() -> size_t {
     if (!store || n_chunks < 0 || n_q <= 0) return 0;
     GatherPlan p;
     if (plan_gather(store, chunk_ids, offsets, n_chunks, pos_mode, n_q, &p)) return 0;
     return gather_ws_bytes(&store->shape, p, n_q);
+    });
 }
 
 extern "C" int tr_prefill_attn_gather(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
@@ -642,6 +688,7 @@ extern "C" int tr_prefill_attn_gather(const tr_store* store, const int32_t* chun
                                       const int32_t* q_pos, int32_t n_q, int64_t cache_capacity_rows, void* out,
                                       void* workspace, size_t workspace_bytes, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     if (!store) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn_gather: store is NULL");
     if (n_chunks < 0 || n_q < 0) return tr_fail(TR_ERR_INVALID_ARG, "negative count");
@@ -703,12 +750,14 @@ extern "C" int tr_prefill_attn_gather(const tr_store* store, const int32_t* chun
     ca.seq[0].n_split = p.n_split;
     ca.seq[0].ws_row0 = 0;
     return tr_launch_gather_attn(a, ca, sh->head_dim, (hipStream_t)stream);
+    });
 }
 
 // ---- one pass over a packed sequence with per-token visible ranges and position ids -----------------------------
 extern "C" int tr_sequence_plan(const int32_t* chunk_lens, int32_t n_chunks, int32_t n_tail, int32_t pos_mode, int32_t tail_start,
                                 int32_t* seg_start, int32_t* pos, int64_t capacity)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     if (n_chunks < 0 || n_tail < 0) return tr_fail(TR_ERR_INVALID_ARG, "negative count");
     if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
@@ -737,11 +786,13 @@ extern "C" int tr_sequence_plan(const int32_t* chunk_lens, int32_t n_chunks, int
         pos[n_doc + i] = (int32_t)(start + i);
     }
     return TR_OK;
+    });
 }
 
 extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* seg_start,
                                         const int32_t* pos, int64_t total_tokens, void* out, void* k_rot_out, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     int rc = tr_check_shape(shape);
     if (rc) return rc;
@@ -779,6 +830,7 @@ extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, co
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)shape->head_dim));
     if (shape->dtype == TR_F32) return tr_launch_blockdiag_attn_f32(a, shape->head_dim, s);
     return tr_launch_blockdiag_attn(a, shape->head_dim, wg_rows, s);
+    });
 }
 
 // ---- decode step: one query token per request ---------------------------------------------------------------------
@@ -794,27 +846,33 @@ int decode_cu(int32_t n_req, std::vector<int32_t>* cu)
 
 extern "C" size_t tr_decode_attn_workspace_size(const tr_shape* shape, const int64_t* cache_row_start, int32_t n_req)
 {
+    return tr_guard_size([&]() -> size_t {
     std::vector<int32_t> cu;
     if (decode_cu(n_req, &cu)) return 0;
     return tr_prefill_attn_batched_workspace_size(shape, cu.data(), cache_row_start, n_req);
+    });
 }
 
 extern "C" int tr_decode_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* q_pos,
                               const int64_t* cache_row_start, int32_t n_req, void* out, void* workspace,
                               size_t workspace_bytes, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     std::vector<int32_t> cu;
     int rc = decode_cu(n_req, &cu);
     if (rc) return rc;
     return tr_prefill_attn_batched(shape, q, k, v, q_pos, cu.data(), cache_row_start, n_req, out, workspace, workspace_bytes, stream);
+    });
 }
 
 // ---- offline chunk prefill --------------------------------------------------------------------------------------------
 extern "C" size_t tr_chunk_prefill_attn_workspace_size(const tr_shape* shape, int64_t total_tokens, int32_t max_chunk_len)
 {
+    return tr_guard_size([&]() -> size_t {
     if (tr_check_shape(shape) || total_tokens <= 0 || max_chunk_len <= 0) return 0;
     return tr_align256((size_t)max_chunk_len * (shape->head_dim / 2) * 16) + tr_align256((size_t)total_tokens * 4);
+    });
 }
 
 extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v,
@@ -822,6 +880,7 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
                                      int32_t max_chunk_len, void* out, void* k_rot_out, void* workspace,
                                      size_t workspace_bytes, void* stream)
 {
+    return tr_guard_int([&]() -> int {
     tr_clear_error();
     int rc = tr_check_shape(shape);
     if (rc) return rc;
@@ -866,4 +925,5 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)shape->head_dim));
     if (shape->dtype == TR_F32) return tr_launch_blockdiag_attn_f32(a, shape->head_dim, s);
     return tr_launch_blockdiag_attn(a, shape->head_dim, wg_rows, s);
+    });
 }

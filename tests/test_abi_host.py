@@ -45,7 +45,7 @@ def test_header_declares_and_library_exports_the_same_symbols(L):
 def test_status_codes_match_header():
     text = open(HEADER).read()
     for name in ["TR_OK", "TR_ERR_INVALID_ARG", "TR_ERR_BAD_CHUNK_ID", "TR_ERR_BAD_PLAN", "TR_ERR_SHAPE",
-                 "TR_ERR_UNSUPPORTED", "TR_ERR_HIP", "TR_ERR_WORKSPACE", "TR_POS_COMPOSITE", "TR_POS_REORDERED",
+                 "TR_ERR_UNSUPPORTED", "TR_ERR_HIP", "TR_ERR_WORKSPACE", "TR_ERR_NO_MEMORY", "TR_POS_COMPOSITE", "TR_POS_REORDERED",
                  "TR_F32", "TR_BF16", "TR_ROPE_INTERLEAVED", "TR_ROPE_HALF"]:
         m = re.search(r"\b%s\s*=\s*(-?\d+)" % name, text)
         assert m, name
