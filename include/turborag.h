@@ -20,9 +20,10 @@
  *   - Every function returns a tr_status (0 = TR_OK, negative = error).  tr_last_error() returns a
  *     thread-local message for the last error on the calling thread.  Nothing throws, aborts or prints.
  *   - Results are deterministic: same inputs, same bits (no atomics in any reduction).
- *   - RoPE follows Eq. 3: pair m = channels (2m, 2m+1) of a head is turned by pos * theta_m,
- *     theta_m = rope_base^(-2m/head_dim).  Only TR_ROPE_INTERLEAVED (the layout Eq. 3 prints) is
- *     implemented; TR_ROPE_HALF returns TR_ERR_UNSUPPORTED.
+ *   - RoPE follows Eq. 3: pair m of a head is turned by pos * theta_m, theta_m = rope_base^(-2m/head_dim).
+ *     TR_ROPE_INTERLEAVED: pair m = channels (2m, 2m+1), the layout Eq. 3 prints.  TR_ROPE_HALF: pair m =
+ *     channels (m, m + head_dim/2), the layout in which the released weights of the models of Sec. 4 keep
+ *     their heads.  Queries, stored keys and new keys of one shape all use that shape's layout.
  *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
  *   - Supported shapes: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads; row counts below 2^31.
  */
@@ -73,7 +74,7 @@ const char* tr_last_error(void);
  * tr_chunk_prefill_attn's k_rot_out).  chunk_row_start: host [n_chunks+1], non-decreasing, chunk c owns rows
  * [chunk_row_start[c], chunk_row_start[c+1]) (empty chunks allowed).  The table is copied; the two device
  * pointers are recorded, not copied, and must outlive the store.  No GPU work.
- * Errors: TR_ERR_INVALID_ARG, TR_ERR_SHAPE, TR_ERR_UNSUPPORTED (rope layout). */
+ * Errors: TR_ERR_INVALID_ARG (also an unknown rope layout), TR_ERR_SHAPE. */
 int tr_store_create(const tr_shape* shape, const void* k_store, const void* v_store,
                     const int64_t* chunk_row_start, int32_t n_chunks, tr_store** out);
 int tr_store_destroy(tr_store* store);

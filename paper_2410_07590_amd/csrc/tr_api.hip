@@ -53,8 +53,7 @@ int tr_check_shape(const tr_shape* s)
         return tr_fail(TR_ERR_SHAPE, "n_q_heads %d must be a positive multiple of n_kv_heads %d", s->n_q_heads, s->n_kv_heads);
     if (s->n_q_heads / s->n_kv_heads > 128) return tr_fail(TR_ERR_SHAPE, "group size above 128");
     if (!(s->rope_base > 1.0) || !isfinite(s->rope_base)) return tr_fail(TR_ERR_SHAPE, "rope_base must be finite and > 1");
-    if (s->rope_layout == TR_ROPE_HALF) return tr_fail(TR_ERR_UNSUPPORTED, "TR_ROPE_HALF is not implemented (Eq. 3 pairs adjacent channels)");
-    if (s->rope_layout != TR_ROPE_INTERLEAVED) return tr_fail(TR_ERR_INVALID_ARG, "rope_layout %d", s->rope_layout);
+    if (s->rope_layout != TR_ROPE_INTERLEAVED && s->rope_layout != TR_ROPE_HALF) return tr_fail(TR_ERR_INVALID_ARG, "rope_layout %d", s->rope_layout);
     if (s->reserved != 0) return tr_fail(TR_ERR_INVALID_ARG, "reserved must be 0");
     return TR_OK;
 }
@@ -166,6 +165,7 @@ int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* o
     a.head_units = sh->head_dim * eb / 16;
     a.span_units = (int32_t)span;
     a.half_dim = sh->head_dim / 2;
+    a.rope_half = tr_rope_half(sh);
     tr_fill_theta(sh, a.theta);
     size_t i = 0;
     while (i < runs.size()) {
@@ -277,6 +277,7 @@ int launch_append(const tr_shape* shape, const void* k_new, const void* v_new, c
     a.cache_v = cache_v;
     a.n_kv_heads = shape->n_kv_heads;
     a.head_dim = shape->head_dim;
+    a.rope_half = tr_rope_half(shape);
     tr_fill_theta(shape, a.theta);
     size_t i = 0;
     while (i < descs.size()) {
@@ -508,6 +509,7 @@ int run_prefix(const tr_shape* sh, const void* q, const void* k, const void* v, 
     a.group = sh->n_q_heads / sh->n_kv_heads;
     a.scale = (float)(1.0 / sqrt((double)sh->head_dim));
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)sh->head_dim));
+    a.rope_half = tr_rope_half(sh);
     tr_fill_theta(sh, a.theta);
     for (int m = 0; m < 64; ++m) a.theta_rev[m] = a.theta[m] / 6.283185307179586476925;
     for (size_t r0 = 0; r0 < reqs.size(); r0 += TR_MAX_SEQ) {
@@ -731,6 +733,7 @@ extern "C" int tr_prefill_attn_gather(const tr_store* store, const int32_t* chun
     a.group = sh->n_q_heads / sh->n_kv_heads;
     a.tok_per_tile = p.tok_per_tile;
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)sh->head_dim));
+    a.rope_half = tr_rope_half(sh);
     double theta[64];
     tr_fill_theta(sh, theta);
     for (int m = 0; m < 64; ++m) a.theta_rev[m] = theta[m] / 6.283185307179586476925;
@@ -823,6 +826,7 @@ extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, co
     a.n_q_heads = shape->n_q_heads;
     a.n_kv_heads = shape->n_kv_heads;
     a.group = shape->n_q_heads / shape->n_kv_heads;
+    a.rope_half = tr_rope_half(shape);
     const int wg_rows = env_int("TR_WG_ROWS", 0) == 256 ? 256 : 128;
     a.tok_per_tile = wg_rows / a.group;
     a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);
@@ -915,6 +919,7 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
     a.n_q_heads = shape->n_q_heads;
     a.n_kv_heads = shape->n_kv_heads;
     a.group = shape->n_q_heads / shape->n_kv_heads;
+    a.rope_half = tr_rope_half(shape);
     // chunks are short (a row tile walks a few key tiles only), so two independent 4-wave workgroups per CU, which
     // overlap one's prologue and epilogue with the other's tile loop, beat one 8-wave workgroup
     const int forced_rows = env_int("TR_WG_ROWS", 0);

@@ -158,11 +158,40 @@ __device__ __forceinline__ void rotate_q_shared(const u32x4 (&raw)[D / 16], LDS_
     }
 }
 
+// Half-split layout: channel c < D/2 pairs with c + D/2, i.e. fragment ks (channels 16 ks + 8 h .. +7) pairs element by
+// element with fragment ks + D/32, and the pair index of element e is 16 ks + 8 h + e.  row: the token slot's table
+// row, sw: twice the slot (the swizzle of its 16-byte chunks).
+template <int D>
+__device__ __forceinline__ void rot_frag_half(const u32x4& lo, const u32x4& hi, LDS_AS const char* row, int ks, int h, int sw,
+                                              bool valid, float sl2e, bf16x8& flo, bf16x8& fhi)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { // two pairs (one 16-byte table chunk) at a time
+        const int ch = (8 * ks + 4 * h + q) ^ sw;
+        const f32x4 cs = *(LDS_AS const f32x4*)(row + ch * 16);
+        const float la = valid ? bf_lo(lo[q]) * sl2e : 0.0f, lb = valid ? bf_hi(lo[q]) * sl2e : 0.0f;
+        const float ha = valid ? bf_lo(hi[q]) * sl2e : 0.0f, hb = valid ? bf_hi(hi[q]) * sl2e : 0.0f;
+        flo[2 * q] = (__bf16)(la * cs[0] - ha * cs[1]);
+        fhi[2 * q] = (__bf16)(ha * cs[0] + la * cs[1]);
+        flo[2 * q + 1] = (__bf16)(lb * cs[2] - hb * cs[3]);
+        fhi[2 * q + 1] = (__bf16)(hb * cs[2] + lb * cs[3]);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void rotate_q_shared_half(const u32x4 (&raw)[D / 16], LDS_AS const char* tab, int slot, int h,
+                                                     bool valid, float sl2e, bf16x8 (&qf)[D / 16])
+{
+    LDS_AS const char* row = tab + slot * (4 * D);
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) rot_frag_half<D>(raw[ks], raw[ks + D / 32], row, ks, h, 2 * slot, valid, sl2e, qf[ks], qf[ks + D / 32]);
+}
+
 // Rotated, scaled queries of a wave from their raw fragments.  slot: which of the wave's tokens this lane's row
 // belongs to (0 .. n_slots-1, n_slots wave-uniform); pos_of_slot(s): position id of the wave's token slot s (any
 // value for slots past the wave's last token).  Tokens go through the table ROT_SLOTS at a time: one pass when the
 // GQA group is >= 4, up to four for smaller groups.
-template <int D, class PosFn>
+template <int D, bool HALF, class PosFn>
 __device__ __forceinline__ void rotate_queries(const u32x4 (&raw)[D / 16], LDS_AS char* tab, double th, int lane, int h, int slot,
                                                int n_slots, bool valid, float sl2e, PosFn pos_of_slot, bf16x8 (&qf)[D / 16])
 {
@@ -171,10 +200,11 @@ __device__ __forceinline__ void rotate_queries(const u32x4 (&raw)[D / 16], LDS_A
         build_rot_table<D>(tab, th, lane, pos_of_slot(p0 + (lane & (ROT_SLOTS - 1))));
         const bool mine = (slot >= p0) && (slot < p0 + ROT_SLOTS);
         bf16x8 f[D / 16];
-        rotate_q_shared<D>(raw, tab, mine ? slot - p0 : 0, h, valid, sl2e, f);
+        if (HALF) rotate_q_shared_half<D>(raw, tab, mine ? slot - p0 : 0, h, valid, sl2e, f);
+        else rotate_q_shared<D>(raw, tab, mine ? slot - p0 : 0, h, valid, sl2e, f);
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks)
-            if (mine || p0 == 0) qf[ks] = f[ks];
+            if (mine || p0 == 0) qf[ks] = f[ks]; // the first pass initialises every lane's fragments
         __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the table is read before the next pass (or a tile load) overwrites it
     }
 }
@@ -397,10 +427,11 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
 // would make its consumer wait for the tiles.  pos_lane: position id of token slot (lane & 7) of this wave, loaded by
 // the caller; pos_of_slot serves the later passes of small GQA groups.  The rotation table sits in stage NS-1, which
 // no tile load targets before the first barrier of the tile loop.
-template <int D, int NW, int NS, class PosFn>
+template <int D, int NW, int NS, bool HALF, class PosFn>
 __device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
                                          const Walk& w, const RowCtx& rc, int pos_lane, int slot, int n_slots, PosFn pos_of_slot,
-                                         const double* theta_rev, float sl2e, LDS_AS char* smem, bf16x8 (&qf)[D / 16])
+                                         const double* theta_rev, float sl2e, LDS_AS char* smem,
+                                         bf16x8 (&qf)[D / 16])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5;
     double th = theta_rev[lane % (D / 2)];
@@ -411,8 +442,8 @@ __device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __b
     issue_prologue<D, NW, NS>(k, v, w, smem, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
     LDS_AS char* tab = smem + (NS - 1) * Geo<D>::STAGE_BYTES + wave * (ROT_SLOTS * 4 * D);
-    rotate_queries<D>(raw, tab, th, lane, h, slot, n_slots, rc.valid, sl2e,
-                      [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
+    rotate_queries<D, HALF>(raw, tab, th, lane, h, slot, n_slots, rc.valid, sl2e,
+                            [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
 }
 
 // Write the wave's 32 x D accumulator as rows: stage O^T through LDS (64 channels at a time) so that every
@@ -465,7 +496,7 @@ __device__ __forceinline__ void store_rows(const Acc<D>& acc, float l_tot, bool 
 }
 
 // ---- step 6: query prefill over the assembled cache -------------------------------------------------------------
-template <int D, int NW, int NS>
+template <int D, int NW, int NS, bool HALF>
 __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
@@ -508,7 +539,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     const Walk w = make_walk(sb, min(se, sd.kv_row0 + n_doc + last_tok + 1), sd.kv_row0 + sd.kv_len - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
+    prologue<D, NW, NS, HALF>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
                         a.theta_rev, a.scale_log2e, smem, qf);
 
     Acc<D> acc;
@@ -544,7 +575,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
 constexpr int GATHER_NW = 4, GATHER_NS = 2;
 template <int D> constexpr int gather_lds_bytes() { return GATHER_NS * Geo<D>::STAGE_BYTES + GATHER_NW * ROT_SLOTS * 4 * D; }
 
-template <int D>
+template <int D, bool HALF>
 __global__ __launch_bounds__(64 * GATHER_NW, 2) void gather_attn_kernel(const TrGatherArgs a)
 {
     using G = Geo<D>;
@@ -640,24 +671,43 @@ __global__ __launch_bounds__(64 * GATHER_NW, 2) void gather_attn_kernel(const Tr
                 const bool mine = (slot >= p0) && (slot < p0 + ROT_SLOTS);
                 LDS_AS const char* row = tab + (mine ? slot - p0 : 0) * (4 * D);
                 const int sw = 2 * (mine ? slot - p0 : 0);
-                // the raw fragments come in two halves so that they never hold more than 16 registers
+                // the raw fragments come in two parts so that they never hold more than 16 registers
+                if (HALF) {
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    u32x4 raw[D / 32];
+                    for (int part = 0; part < 2; ++part) {
+                        u32x4 qlo[D / 64], qhi[D / 64];
 #pragma unroll
-                    for (int i = 0; i < D / 32; ++i) raw[i] = *(const u32x4*)(qrow + 16 * (half * (D / 32) + i));
+                        for (int i = 0; i < D / 64; ++i) {
+                            qlo[i] = *(const u32x4*)(qrow + 16 * (part * (D / 64) + i));
+                            qhi[i] = *(const u32x4*)(qrow + 16 * (part * (D / 64) + i + D / 32));
+                        }
 #pragma unroll
-                    for (int i = 0; i < D / 32; ++i) {
-                        const int ks = half * (D / 32) + i;
-                        const int ch = (2 * (2 * ks + h)) ^ sw;
-                        const f32x4 cs0 = *(LDS_AS const f32x4*)(row + ch * 16);
-                        const f32x4 cs1 = *(LDS_AS const f32x4*)(row + ch * 16 + 16);
-                        bf16x8 f;
-                        rot_pair(raw[i][0], cs0[0], cs0[1], a.scale_log2e, rc.valid, f, 0);
-                        rot_pair(raw[i][1], cs0[2], cs0[3], a.scale_log2e, rc.valid, f, 1);
-                        rot_pair(raw[i][2], cs1[0], cs1[1], a.scale_log2e, rc.valid, f, 2);
-                        rot_pair(raw[i][3], cs1[2], cs1[3], a.scale_log2e, rc.valid, f, 3);
-                        if (mine || p0 == 0) qf[ks] = f;
+                        for (int i = 0; i < D / 64; ++i) {
+                            const int ks = part * (D / 64) + i;
+                            bf16x8 flo, fhi;
+                            rot_frag_half<D>(qlo[i], qhi[i], row, ks, h, sw, rc.valid, a.scale_log2e, flo, fhi);
+                            if (mine || p0 == 0) { qf[ks] = flo; qf[ks + D / 32] = fhi; }
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int part = 0; part < 2; ++part) {
+                        u32x4 raw[D / 32];
+#pragma unroll
+                        for (int i = 0; i < D / 32; ++i) raw[i] = *(const u32x4*)(qrow + 16 * (part * (D / 32) + i));
+#pragma unroll
+                        for (int i = 0; i < D / 32; ++i) {
+                            const int ks = part * (D / 32) + i;
+                            const int ch = (2 * (2 * ks + h)) ^ sw;
+                            const f32x4 cs0 = *(LDS_AS const f32x4*)(row + ch * 16);
+                            const f32x4 cs1 = *(LDS_AS const f32x4*)(row + ch * 16 + 16);
+                            bf16x8 f;
+                            rot_pair(raw[i][0], cs0[0], cs0[1], a.scale_log2e, rc.valid, f, 0);
+                            rot_pair(raw[i][1], cs0[2], cs0[3], a.scale_log2e, rc.valid, f, 1);
+                            rot_pair(raw[i][2], cs1[0], cs1[1], a.scale_log2e, rc.valid, f, 2);
+                            rot_pair(raw[i][3], cs1[2], cs1[3], a.scale_log2e, rc.valid, f, 3);
+                            if (mine || p0 == 0) qf[ks] = f;
+                        }
                     }
                 }
                 __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the table is read before the next pass rewrites it
@@ -706,7 +756,7 @@ constexpr int SHORT_NW = 4, SHORT_NS = 2, SHORT_KT = 32 * SHORT_NW;
 template <int D> constexpr int short_stage_bytes() { return 2 * SHORT_KT * D * 2; }
 template <int D> constexpr int short_merge_row_bytes() { return D * 4 + 16; }
 
-template <int D>
+template <int D, bool HALF>
 __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPrefixArgs a)
 {
     using G = Geo<D>;
@@ -767,8 +817,8 @@ __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPr
     bf16x8 qf[D / 16];
     {
         LDS_AS char* tab = smem + STAGE + wave * (ROT_SLOTS * 4 * D); // stage 1 is free until the first barrier
-        rotate_queries<D>(raw, tab, th, lane, h, slot, n_slots, rc.valid, a.scale_log2e,
-                          [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
+        rotate_queries<D, HALF>(raw, tab, th, lane, h, slot, n_slots, rc.valid, a.scale_log2e,
+                                [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
     }
 
     Acc<D> acc;
@@ -972,7 +1022,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
 // every token can only give wrong numbers, never an access outside the tensors.
 __device__ __forceinline__ int chunk_start(const int32_t* tok_start, int t) { return min(max(tok_start[t], 0), t); }
 
-template <int D, int NW, int NS>
+template <int D, int NW, int NS, bool HALF>
 __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBlockDiagArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
@@ -1020,7 +1070,7 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     const Walk w = make_walk(lo_first, t_last + 1, T - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    prologue<D, NW, NS>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
+    prologue<D, NW, NS, HALF>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
                         a.theta_rev, a.scale_log2e, smem, qf);
 
     Acc<D> acc;
@@ -1046,10 +1096,10 @@ template <int D, int NW, int NS> constexpr int smem_bytes()
     return stages > staging ? stages : staging;
 }
 
-template <int D, int NW, int NS>
+template <int D, int NW, int NS, bool HALF>
 int launch_prefix(const TrPrefixArgs& a, hipStream_t s)
 {
-    auto kern = prefix_attn_kernel<D, NW, NS>;
+    auto kern = prefix_attn_kernel<D, NW, NS, HALF>;
     constexpr int lds = smem_bytes<D, NW, NS>();
     static bool configured = false;
     if (!configured) {
@@ -1061,10 +1111,10 @@ int launch_prefix(const TrPrefixArgs& a, hipStream_t s)
     return TR_OK;
 }
 
-template <int D>
+template <int D, bool HALF>
 int launch_short(const TrPrefixArgs& a, hipStream_t s)
 {
-    auto kern = short_attn_kernel<D>;
+    auto kern = short_attn_kernel<D, HALF>;
     constexpr int ring = SHORT_NS * short_stage_bytes<D>();
     constexpr int merge = SHORT_NW * 32 * short_merge_row_bytes<D>() + SHORT_NW * 32 * 8;
     constexpr int lds = ring > merge ? ring : merge;
@@ -1078,10 +1128,10 @@ int launch_short(const TrPrefixArgs& a, hipStream_t s)
     return TR_OK;
 }
 
-template <int D>
+template <int D, bool HALF>
 int launch_gather(const TrGatherArgs& a, hipStream_t s)
 {
-    auto kern = gather_attn_kernel<D>;
+    auto kern = gather_attn_kernel<D, HALF>;
     constexpr int staging = GATHER_NW * 32 * (64 * 4 + 16);
     constexpr int lds = gather_lds_bytes<D>() > staging ? gather_lds_bytes<D>() : staging;
     static bool configured = false;
@@ -1094,10 +1144,10 @@ int launch_gather(const TrGatherArgs& a, hipStream_t s)
     return TR_OK;
 }
 
-template <int D, int NW, int NS>
+template <int D, int NW, int NS, bool HALF>
 int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
 {
-    auto kern = blockdiag_attn_kernel<D, NW, NS>;
+    auto kern = blockdiag_attn_kernel<D, NW, NS, HALF>;
     constexpr int lds = smem_bytes<D, NW, NS>();
     static bool configured = false;
     if (!configured) {
@@ -1109,6 +1159,21 @@ int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
     return TR_OK;
 }
 
+template <bool HALF>
+int prefix_dispatch(const TrPrefixArgs& a, int head_dim, int wg_rows, hipStream_t s)
+{
+    if (wg_rows == 32) return head_dim == 128 ? launch_short<128, HALF>(a, s) : launch_short<64, HALF>(a, s);
+    if (head_dim == 128) return wg_rows == 256 ? launch_prefix<128, 8, 4, HALF>(a, s) : launch_prefix<128, 4, 2, HALF>(a, s);
+    return wg_rows == 256 ? launch_prefix<64, 8, 4, HALF>(a, s) : launch_prefix<64, 4, 2, HALF>(a, s);
+}
+
+template <bool HALF>
+int blockdiag_dispatch(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s)
+{
+    if (head_dim == 128) return wg_rows == 256 ? launch_blockdiag<128, 8, 4, HALF>(a, s) : launch_blockdiag<128, 4, 2, HALF>(a, s);
+    return wg_rows == 256 ? launch_blockdiag<64, 8, 4, HALF>(a, s) : launch_blockdiag<64, 4, 2, HALF>(a, s);
+}
+
 } // namespace
 
 // wg_rows: 128 (4 waves, 2-stage ring, two workgroups per CU), 256 (8 waves, 4-stage ring, one per CU) or 32 (the
@@ -1116,10 +1181,7 @@ int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
 int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool any_split, int total_rows, hipStream_t s)
 {
     if (a.n_items <= 0) return TR_OK;
-    int rc;
-    if (wg_rows == 32) rc = head_dim == 128 ? launch_short<128>(a, s) : launch_short<64>(a, s);
-    else if (head_dim == 128) rc = wg_rows == 256 ? launch_prefix<128, 8, 4>(a, s) : launch_prefix<128, 4, 2>(a, s);
-    else rc = wg_rows == 256 ? launch_prefix<64, 8, 4>(a, s) : launch_prefix<64, 4, 2>(a, s);
+    const int rc = a.rope_half ? prefix_dispatch<true>(a, head_dim, wg_rows, s) : prefix_dispatch<false>(a, head_dim, wg_rows, s);
     if (rc) return rc;
     if (any_split) {
         const int rows_per_block = 256 / 32;
@@ -1134,7 +1196,9 @@ int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool
 int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_args, int head_dim, hipStream_t s)
 {
     if (a.n_items <= 0) return TR_OK;
-    int rc = head_dim == 128 ? launch_gather<128>(a, s) : launch_gather<64>(a, s);
+    int rc;
+    if (a.rope_half) rc = head_dim == 128 ? launch_gather<128, true>(a, s) : launch_gather<64, true>(a, s);
+    else rc = head_dim == 128 ? launch_gather<128, false>(a, s) : launch_gather<64, false>(a, s);
     if (rc) return rc;
     if (a.n_split > 1) {
         const int total_rows = a.n_q * a.n_q_heads;
@@ -1149,6 +1213,5 @@ int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_arg
 int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s)
 {
     if (a.total_tokens <= 0) return TR_OK;
-    if (head_dim == 128) return wg_rows == 256 ? launch_blockdiag<128, 8, 4>(a, s) : launch_blockdiag<128, 4, 2>(a, s);
-    return wg_rows == 256 ? launch_blockdiag<64, 8, 4>(a, s) : launch_blockdiag<64, 4, 2>(a, s);
+    return a.rope_half ? blockdiag_dispatch<true>(a, head_dim, wg_rows, s) : blockdiag_dispatch<false>(a, head_dim, wg_rows, s);
 }

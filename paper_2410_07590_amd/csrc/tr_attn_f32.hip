@@ -16,7 +16,7 @@ struct F32Row {
 
 template <int D>
 __device__ __forceinline__ void attn_f32_row(const F32Row& r, const float* __restrict__ k, const float* __restrict__ v,
-                                             int n_kv_heads, const double* theta, float scale)
+                                             int n_kv_heads, const double* theta, float scale, int rope_half)
 {
     __shared__ float qs[D];
     __shared__ float ps[256];
@@ -24,9 +24,10 @@ __device__ __forceinline__ void attn_f32_row(const F32Row& r, const float* __res
     for (int m = lane; m < D / 2; m += 64) {
         double sn, cn;
         sincos(r.pos * theta[m], &sn, &cn);
-        const double xa = (double)r.q[2 * m], xb = (double)r.q[2 * m + 1];
-        qs[2 * m] = (float)(xa * cn - xb * sn);
-        qs[2 * m + 1] = (float)(xb * cn + xa * sn);
+        const int ia = rope_half ? m : 2 * m, ib = rope_half ? m + D / 2 : 2 * m + 1; // the pair's two channels
+        const double xa = (double)r.q[ia], xb = (double)r.q[ib];
+        qs[ia] = (float)(xa * cn - xb * sn);
+        qs[ib] = (float)(xb * cn + xa * sn);
     }
     __syncthreads();
     constexpr int CPL = D / 64; // channels per lane
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(64) void prefix_attn_f32_kernel(const TrPrefixArgs 
     r.key_hi = sd.kv_row0 + (sd.kv_len - sd.n_q) + i;
     r.kvh = hq / a.group;
     r.pos = (double)a.q_pos[tq];
-    attn_f32_row<D>(r, (const float*)a.k, (const float*)a.v, a.n_kv_heads, a.theta, a.scale);
+    attn_f32_row<D>(r, (const float*)a.k, (const float*)a.v, a.n_kv_heads, a.theta, a.scale, a.rope_half);
 }
 
 template <int D>
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(64) void blockdiag_attn_f32_kernel(const TrBlockDia
     r.key_hi = t;
     r.kvh = hq / a.group;
     r.pos = a.pos ? (double)a.pos[t] : (double)(t - r.key_lo);
-    attn_f32_row<D>(r, (const float*)a.k, (const float*)a.v, a.n_kv_heads, a.theta, a.scale);
+    attn_f32_row<D>(r, (const float*)a.k, (const float*)a.v, a.n_kv_heads, a.theta, a.scale, a.rope_half);
 }
 
 } // namespace

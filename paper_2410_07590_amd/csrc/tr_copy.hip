@@ -63,6 +63,48 @@ template <> struct Unit<TR_BF16> {
     }
 };
 
+// Half-split layout: channel c < d/2 pairs with c + d/2, so a unit of the low half pairs element by element with
+// the unit d/2 channels further on.  me / partner: the two units, low: whether `me` is the low half; c, s: the
+// (cos, sin) of the ELEMS pair indices the unit covers.  y_lo = x_lo c - x_hi s, y_hi = x_hi c + x_lo s.
+template <int DTYPE> struct UnitHalf;
+template <> struct UnitHalf<TR_BF16> {
+    static constexpr int ELEMS = 8;
+    __device__ static __forceinline__ uint4 rotate(uint4 me, uint4 partner, bool low, const double* c, const double* s)
+    {
+        uint32_t a[4] = {me.x, me.y, me.z, me.w}, b[4] = {partner.x, partner.y, partner.z, partner.w};
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            uint32_t r[2];
+#pragma unroll
+            for (int hw = 0; hw < 2; ++hw) {
+                const double xm = bf16_bits_to_double(hw ? a[p] >> 16 : a[p] & 0xffffu);
+                const double xp = bf16_bits_to_double(hw ? b[p] >> 16 : b[p] & 0xffffu);
+                const double t0 = __dmul_rn(xm, c[2 * p + hw]), t1 = __dmul_rn(xp, s[2 * p + hw]);
+                r[hw] = double_to_bf16_bits(low ? __dsub_rn(t0, t1) : __dadd_rn(t0, t1));
+            }
+            a[p] = r[0] | (r[1] << 16);
+        }
+        return make_uint4(a[0], a[1], a[2], a[3]);
+    }
+};
+template <> struct UnitHalf<TR_F32> {
+    static constexpr int ELEMS = 4;
+    __device__ static __forceinline__ uint4 rotate(uint4 me, uint4 partner, bool low, const double* c, const double* s)
+    {
+        uint32_t a[4] = {me.x, me.y, me.z, me.w}, b[4] = {partner.x, partner.y, partner.z, partner.w};
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const double t0 = __dmul_rn((double)__uint_as_float(a[p]), c[p]), t1 = __dmul_rn((double)__uint_as_float(b[p]), s[p]);
+            a[p] = __float_as_uint(__double2float_rn(low ? __dsub_rn(t0, t1) : __dadd_rn(t0, t1)));
+        }
+        return make_uint4(a[0], a[1], a[2], a[3]);
+    }
+};
+__device__ __forceinline__ uint4 shfl_xor_u4(uint4 x, int mask)
+{
+    return make_uint4(__shfl_xor(x.x, mask), __shfl_xor(x.y, mask), __shfl_xor(x.z, mask), __shfl_xor(x.w, mask));
+}
+
 template <> struct Unit<TR_F32> {
     static constexpr int PAIRS = 2;
     __device__ static __forceinline__ uint4 rotate(uint4 x, const double* c, const double* s)
@@ -88,16 +130,68 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p)
     return make_uint4(r[0], r[1], r[2], r[3]);
 }
 
+constexpr int APPEND_MAX_HEADS = 16; // KV heads held in registers at once; more go round the loop again
+
+// The same for the half-split layout: the pair is (channel m, channel m + d/2) of every head.
+template <int DTYPE>
+__device__ __forceinline__ void append_pair_half(const void* k_new, const void* v_new, const int32_t* q_pos, void* cache_k,
+                                                 void* cache_v, int n_kv_heads, int half, double theta_m, int64_t src_row,
+                                                 int64_t dst_row, int m)
+{
+    typedef typename std::conditional<DTYPE == TR_BF16, uint16_t, float>::type Elem;
+    const int d = 2 * half;
+    const Elem* ks = (const Elem*)k_new + src_row * n_kv_heads * d + m;
+    const Elem* vs = (const Elem*)v_new + src_row * n_kv_heads * d + m;
+    Elem* kd = (Elem*)cache_k + dst_row * n_kv_heads * d + m;
+    Elem* vd = (Elem*)cache_v + dst_row * n_kv_heads * d + m;
+    const double angle = (double)q_pos[src_row] * theta_m;
+    double sn = 0.0, cn = 1.0;
+    for (int h0 = 0; h0 < n_kv_heads; h0 += APPEND_MAX_HEADS) {
+        Elem ka[APPEND_MAX_HEADS], kb[APPEND_MAX_HEADS], va[APPEND_MAX_HEADS], vb[APPEND_MAX_HEADS];
+#pragma unroll
+        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
+            if (h0 + j < n_kv_heads) {
+                ka[j] = ks[(h0 + j) * d];
+                kb[j] = ks[(h0 + j) * d + half];
+                if (v_new) { va[j] = vs[(h0 + j) * d]; vb[j] = vs[(h0 + j) * d + half]; }
+            }
+        if (h0 == 0) sincos(angle, &sn, &cn);
+#pragma unroll
+        for (int j = 0; j < APPEND_MAX_HEADS; ++j)
+            if (h0 + j < n_kv_heads) {
+                double xa, xb, ya, yb;
+                if constexpr (DTYPE == TR_BF16) {
+                    xa = bf16_bits_to_double(ka[j]);
+                    xb = bf16_bits_to_double(kb[j]);
+                } else {
+                    xa = (double)ka[j];
+                    xb = (double)kb[j];
+                }
+                rotate_pair(xa, xb, cn, sn, ya, yb);
+                if constexpr (DTYPE == TR_BF16) {
+                    kd[(h0 + j) * d] = (uint16_t)double_to_bf16_bits(ya);
+                    kd[(h0 + j) * d + half] = (uint16_t)double_to_bf16_bits(yb);
+                } else {
+                    kd[(h0 + j) * d] = __double2float_rn(ya);
+                    kd[(h0 + j) * d + half] = __double2float_rn(yb);
+                }
+                if (v_new) { vd[(h0 + j) * d] = va[j]; vd[(h0 + j) * d + half] = vb[j]; }
+            }
+    }
+}
+
 // ---- one (token, pair m) of the query append: K' rotated at q_pos, V copied, for every KV head ----------------
 // The angle is shared by all KV heads of the token (the fp64 sincos is by far the longest thing a thread does, so
 // it is done once per thread), and the loads go out before it.
-constexpr int APPEND_MAX_HEADS = 16; // KV heads held in registers at once; more go round the loop again
-
-template <int DTYPE>
+template <int DTYPE, bool HALF>
 __device__ __forceinline__ void append_pair(const void* k_new, const void* v_new, const int32_t* q_pos, void* cache_k,
                                             void* cache_v, int n_kv_heads, int half, double theta_m, int64_t src_row,
                                             int64_t dst_row, int m)
 {
+    if constexpr (HALF) {
+        append_pair_half<DTYPE>(k_new, v_new, q_pos, cache_k, cache_v, n_kv_heads, half, theta_m, src_row, dst_row, m);
+        return;
+    }
     typedef typename std::conditional<DTYPE == TR_BF16, uint32_t, float2>::type Pair; // one (even, odd) channel pair
     const Pair* ks = (const Pair*)k_new + src_row * n_kv_heads * half + m;
     const Pair* vs = (const Pair*)v_new + src_row * n_kv_heads * half + m;
@@ -150,7 +244,7 @@ __device__ __forceinline__ void st_stream(uint4* p, uint4 x)
 #endif
 }
 
-template <int DTYPE>
+template <int DTYPE, bool HALF>
 __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
 {
     __shared__ double cs[64][2];
@@ -160,8 +254,8 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
         const int gid = (b - a.app.first_block) * 256 + (int)threadIdx.x;
         const int tok = gid / a.half_dim, m = gid % a.half_dim;
         if (tok < a.app.n_q)
-            append_pair<DTYPE>(a.app.k_new, a.app.v_new, a.app.q_pos, a.k_dst, a.v_dst, a.app.n_kv_heads, a.half_dim, a.theta[m],
-                               tok, (int64_t)a.app.dst_row0 + tok, m);
+            append_pair<DTYPE, HALF>(a.app.k_new, a.app.v_new, a.app.q_pos, a.k_dst, a.v_dst, a.app.n_kv_heads, a.half_dim,
+                                     a.theta[m], tok, (int64_t)a.app.dst_row0 + tok, m);
         return;
     }
     int lo = 0, hi = a.n_desc - 1;
@@ -190,9 +284,12 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
         if (uu < u1) { kx[i] = ld_stream(ks + uu); vx[i] = ld_stream(vs + uu); }
     }
 
-    constexpr int P = Unit<DTYPE>::PAIRS;
-    double c[P], s[P];
+    constexpr int P = Unit<DTYPE>::PAIRS, E = UnitHalf<DTYPE>::ELEMS;
+    double c[HALF ? E : P], s[HALF ? E : P];
     const bool rot = d.delta != 0;
+    const int hu = (int)((u0 + tid) % a.head_units); // unit inside its head: the same for every unit this thread moves
+    const int hmask = a.head_units >> 1;             // lane distance to the unit d/2 channels away
+    const bool low = hu < hmask;
     if (rot) {
         if (tid < a.half_dim) {
             double sn, cn;
@@ -201,17 +298,30 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
             cs[tid][1] = sn;
         }
         __syncthreads();
-        const int m0 = (int)((u0 + tid) % a.head_units) * P;
+        if constexpr (HALF) {
+            const int m0 = (low ? hu : hu - hmask) * E;
 #pragma unroll
-        for (int p = 0; p < P; ++p) { c[p] = cs[m0 + p][0]; s[p] = cs[m0 + p][1]; }
+            for (int p = 0; p < E; ++p) { c[p] = cs[m0 + p][0]; s[p] = cs[m0 + p][1]; }
+        } else {
+            const int m0 = hu * P;
+#pragma unroll
+            for (int p = 0; p < P; ++p) { c[p] = cs[m0 + p][0]; s[p] = cs[m0 + p][1]; }
+        }
     }
 
     while (u < u1) {
 #pragma unroll
         for (int i = 0; i < ASM_UNROLL; ++i) {
             const int64_t uu = u + 256 * i;
+            // the 16-byte units of one head sit in neighbouring lanes and runs are whole rows, so a lane and the lane
+            // that holds its partner unit are always in this branch together
             if (uu < u1) {
-                st_stream(kd + uu, rot ? Unit<DTYPE>::rotate(kx[i], c, s) : kx[i]);
+                uint4 y = kx[i];
+                if (rot) {
+                    if constexpr (HALF) y = UnitHalf<DTYPE>::rotate(kx[i], shfl_xor_u4(kx[i], hmask), low, c, s);
+                    else y = Unit<DTYPE>::rotate(kx[i], c, s);
+                }
+                st_stream(kd + uu, y);
                 st_stream(vd + uu, vx[i]);
             }
         }
@@ -225,7 +335,7 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
 }
 
 // ---- query append: cache rows of the query tokens (K' rotated at q_pos, V copied) -------------------------
-template <int DTYPE>
+template <int DTYPE, bool HALF>
 __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
 {
     const int half = a.head_dim >> 1;
@@ -236,8 +346,8 @@ __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
     int r = 0, base = 0;
     while (r + 1 < a.n_desc && tok >= base + a.desc[r].n_q) { base += a.desc[r].n_q; ++r; }
     const int i = tok - base;
-    append_pair<DTYPE>(a.k_new, a.v_new, a.q_pos, a.cache_k, a.cache_v, a.n_kv_heads, half, a.theta[m],
-                       (int64_t)a.desc[r].q_row0 + i, (int64_t)a.desc[r].dst_row0 + i, m);
+    append_pair<DTYPE, HALF>(a.k_new, a.v_new, a.q_pos, a.cache_k, a.cache_v, a.n_kv_heads, half, a.theta[m],
+                             (int64_t)a.desc[r].q_row0 + i, (int64_t)a.desc[r].dst_row0 + i, m);
 }
 
 // ---- offline key rotation (Sec. 3.4 step 2): K' = R(t - cu[c]) k -------------------------------------------
@@ -260,12 +370,13 @@ __global__ __launch_bounds__(256) void rope_table_kernel(double2* table, int n_p
 // row of its chunk.
 constexpr int ROPE_ROWS_HEADS = 8; // KV heads in flight per thread
 
-template <int DTYPE>
+template <int DTYPE, bool HALF>
 __global__ __launch_bounds__(256) void rope_rows_kernel(const uint4* k, uint4* k_rot, const int32_t* cu, int32_t* tok_start,
                                                         const double2* table, int table_rows, int64_t total_tokens,
                                                         int n_kv_heads, int head_units, int half_dim)
 {
-    constexpr int P = Unit<DTYPE>::PAIRS;
+    constexpr int P = Unit<DTYPE>::PAIRS, E = UnitHalf<DTYPE>::ELEMS;
+    const int hmask = head_units >> 1;
     const int chunk = blockIdx.y;
     int start = cu[chunk], end = cu[chunk + 1];
     if (start < 0) start = 0;
@@ -284,16 +395,26 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(const uint4* k, uint4* k
 #pragma unroll
             for (int j = 0; j < ROPE_ROWS_HEADS; ++j)
                 if (h0 + j < n_kv_heads) x[j] = ld_stream(src + (h0 + j) * head_units);
-            double c[P], s[P];
+            constexpr int N_CS = HALF ? E : P; // pairs this thread's unit takes part in
+            double c[N_CS], s[N_CS];
+            const bool low = unit < hmask;
+            const int m0 = HALF ? (low ? unit : unit - hmask) * E : unit * P;
 #pragma unroll
-            for (int p = 0; p < P; ++p) {
-                const double2 e = table[(int64_t)pos * half_dim + unit * P + p];
+            for (int p = 0; p < N_CS; ++p) {
+                const double2 e = table[(int64_t)pos * half_dim + m0 + p];
                 c[p] = e.x;
                 s[p] = e.y;
             }
+            // a token's units sit in neighbouring lanes (head_units of them, a power of two), so the partner lane of the
+            // half-split layout is in this iteration too
 #pragma unroll
             for (int j = 0; j < ROPE_ROWS_HEADS; ++j)
-                if (h0 + j < n_kv_heads) dst[(h0 + j) * head_units] = (pos == 0) ? x[j] : Unit<DTYPE>::rotate(x[j], c, s);
+                if (h0 + j < n_kv_heads) {
+                    uint4 y = x[j];
+                    if constexpr (HALF) y = UnitHalf<DTYPE>::rotate(x[j], shfl_xor_u4(x[j], hmask), low, c, s);
+                    else if (pos != 0) y = Unit<DTYPE>::rotate(x[j], c, s);
+                    dst[(h0 + j) * head_units] = y;
+                }
         }
     }
 }
@@ -303,8 +424,9 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(const uint4* k, uint4* k
 int tr_launch_assemble(const TrAssembleArgs& a, int dtype, int n_blocks, hipStream_t s)
 {
     if (n_blocks <= 0) return TR_OK;
-    if (dtype == TR_BF16) hipLaunchKernelGGL(assemble_kernel<TR_BF16>, dim3(n_blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(assemble_kernel<TR_F32>, dim3(n_blocks), dim3(256), 0, s, a);
+    auto kern = dtype == TR_BF16 ? (a.rope_half ? assemble_kernel<TR_BF16, true> : assemble_kernel<TR_BF16, false>)
+                                 : (a.rope_half ? assemble_kernel<TR_F32, true> : assemble_kernel<TR_F32, false>);
+    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(256), 0, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;
 }
@@ -314,8 +436,9 @@ int tr_launch_append(const TrAppendArgs& a, int dtype, hipStream_t s)
     int64_t threads = (int64_t)a.total_tokens * (a.head_dim / 2);
     if (threads <= 0) return TR_OK;
     int blocks = (int)((threads + 255) / 256);
-    if (dtype == TR_BF16) hipLaunchKernelGGL(append_kernel<TR_BF16>, dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(append_kernel<TR_F32>, dim3(blocks), dim3(256), 0, s, a);
+    auto kern = dtype == TR_BF16 ? (a.rope_half ? append_kernel<TR_BF16, true> : append_kernel<TR_BF16, false>)
+                                 : (a.rope_half ? append_kernel<TR_F32, true> : append_kernel<TR_F32, false>);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;
 }
@@ -346,12 +469,11 @@ int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chu
     for (int c0 = 0; c0 < n_chunks; c0 += 65535) {
         const int nc = n_chunks - c0 < 65535 ? n_chunks - c0 : 65535;
         dim3 grid((unsigned)row_blocks, (unsigned)nc);
-        if (shape->dtype == TR_BF16)
-            hipLaunchKernelGGL(rope_rows_kernel<TR_BF16>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu + c0, tok_start,
-                               (const double2*)table, table_rows, total_tokens, shape->n_kv_heads, head_units, shape->head_dim / 2);
-        else
-            hipLaunchKernelGGL(rope_rows_kernel<TR_F32>, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu + c0, tok_start,
-                               (const double2*)table, table_rows, total_tokens, shape->n_kv_heads, head_units, shape->head_dim / 2);
+        const bool half = tr_rope_half(shape) != 0;
+        auto kern = shape->dtype == TR_BF16 ? (half ? rope_rows_kernel<TR_BF16, true> : rope_rows_kernel<TR_BF16, false>)
+                                            : (half ? rope_rows_kernel<TR_F32, true> : rope_rows_kernel<TR_F32, false>);
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, (const uint4*)k, (uint4*)k_rot, cu + c0, tok_start, (const double2*)table,
+                           table_rows, total_tokens, shape->n_kv_heads, head_units, shape->head_dim / 2);
         TR_HIP(hipGetLastError());
     }
     return TR_OK;

@@ -62,7 +62,7 @@ struct TrAssembleArgs {
     int32_t head_units; // 16-byte units per head
     int32_t span_units; // units of K (and of V) one block moves; multiple of 256
     int32_t half_dim;   // head_dim / 2
-    int32_t pad_;
+    int32_t rope_half;  // 1: pairs are (m, m + d/2) instead of (2m, 2m+1)
     double theta[64];
     TrAppendTail app;
     TrCopyDesc desc[TR_MAX_COPY_DESC];
@@ -85,6 +85,8 @@ struct TrAppendArgs {
     int32_t n_kv_heads;
     int32_t head_dim;
     int32_t total_tokens; // tokens covered by this launch (sum of n_q)
+    int32_t rope_half;
+    int32_t pad_;
     double theta[64];
     TrAppendDesc desc[TR_MAX_APPEND_DESC];
 };
@@ -119,6 +121,8 @@ struct TrPrefixArgs {
     int32_t tok_per_tile;
     float scale_log2e; // log2(e) / sqrt(head_dim)
     float scale;       // 1 / sqrt(head_dim)
+    int32_t rope_half;
+    int32_t pad_;
     double theta_rev[64]; // theta_m / (2 pi): position * theta_rev = angle in revolutions
     double theta[64];
     TrSeqDesc seq[TR_MAX_SEQ];
@@ -158,7 +162,7 @@ struct TrGatherArgs {
     int32_t group;
     int32_t tok_per_tile;
     float scale_log2e;
-    float pad_;
+    int32_t rope_half;
     double theta_rev[64];
     TrGatherSeg seg[TR_MAX_GATHER_SEG];
 };
@@ -178,9 +182,15 @@ struct TrBlockDiagArgs {
     int32_t tok_per_tile;
     float scale_log2e;
     float scale;
+    int32_t rope_half;
+    int32_t pad_;
     double theta_rev[64];
     double theta[64];
 };
+
+static_assert(sizeof(TrAssembleArgs) <= 4096 && sizeof(TrAppendArgs) <= 4096 && sizeof(TrPrefixArgs) <= 4096 &&
+                  sizeof(TrGatherArgs) <= 4096 && sizeof(TrBlockDiagArgs) <= 4096,
+              "kernel argument blocks must fit the 4 KB kernarg segment");
 
 // ---- launchers implemented in the .hip files --------------------------------------------------------------
 int tr_launch_assemble(const TrAssembleArgs& a, int dtype, int n_blocks, hipStream_t s);
@@ -190,6 +200,7 @@ int tr_launch_prefix_attn_f32(const TrPrefixArgs& a, int head_dim, int total_row
 int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* theta, hipStream_t s);
 int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int max_chunk_len, int32_t* tok_start,
                         const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s);
+static inline int tr_rope_half(const tr_shape* s) { return s->rope_layout == TR_ROPE_HALF ? 1 : 0; }
 int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s);
 int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_args, int head_dim, hipStream_t s);
 int tr_launch_blockdiag_attn_f32(const TrBlockDiagArgs& a, int head_dim, hipStream_t s);

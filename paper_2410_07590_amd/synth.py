@@ -35,6 +35,7 @@ class Shape:
     head_dim: int
     dtype: str          # "f32" | "bf16"
     rope_base: float
+    rope_layout: int = 0   # 0: pair m = channels (2m, 2m+1); 1: pair m = channels (m, m + head_dim/2)
 
     @property
     def torch_dtype(self):

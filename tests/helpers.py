@@ -42,7 +42,7 @@ def assert_same_bits(got, want, what, max_mismatch_frac=0.0):
 
 
 def gpu_shape(B, sh):
-    return B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    return B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base, sh.rope_layout)
 
 
 def run_request_gpu(B, sh, store_dev, req, slack_rows=0):
@@ -68,7 +68,7 @@ def run_request_gpu(B, sh, store_dev, req, slack_rows=0):
 
 def run_request_oracle(sh, store, req, rows=None):
     return oracle.online_prefill(bits(store.k), bits(store.v), store.row_start, req.chunk_ids, req.pos_mode,
-                                 bits(req.q), bits(req.k_q), bits(req.v_q), req.q_pos, sh.rope_base, rows=rows)
+                                 bits(req.q), bits(req.k_q), bits(req.v_q), req.q_pos, sh.rope_base, layout=sh.rope_layout, rows=rows)
 
 
 def check_request(B, sh, store, store_dev, req, rows=None, k_mismatch_frac=1e-5):

@@ -75,7 +75,7 @@ def _i64(a):
 
 def test_shape_validation(L):
     bad = [(_shape(hq=28, hkv=5), B.TR_ERR_SHAPE), (_shape(d=96), B.TR_ERR_SHAPE), (_shape(hq=0), B.TR_ERR_SHAPE),
-           (_shape(dtype=7), B.TR_ERR_SHAPE), (_shape(layout=B.TR_ROPE_HALF), B.TR_ERR_UNSUPPORTED),
+           (_shape(dtype=7), B.TR_ERR_SHAPE), (_shape(layout=7), B.TR_ERR_INVALID_ARG),
            (_shape(base=0.0), B.TR_ERR_SHAPE)]
     for sh, want in bad:
         rc, h = _store(L, sh, [0, 4])
@@ -274,7 +274,8 @@ def test_chunk_prefill_validation(L):
     assert call(ws_bytes=size - 256) == B.TR_ERR_WORKSPACE
     assert call(max_len=0) == B.TR_ERR_INVALID_ARG
     assert call(n_chunks=-1) == B.TR_ERR_INVALID_ARG
-    assert call(shape=_shape(32, 8, 128, B.TR_BF16, 5e5, B.TR_ROPE_HALF)) == B.TR_ERR_UNSUPPORTED
+    assert call(shape=_shape(32, 8, 128, B.TR_BF16, 5e5, 9)) == B.TR_ERR_INVALID_ARG                  # unknown rope layout
+    assert call(shape=_shape(32, 8, 128, B.TR_BF16, 5e5, B.TR_ROPE_HALF), total=0, n_chunks=0) == B.TR_OK
     assert call(total=0, n_chunks=0) == B.TR_OK
 
 

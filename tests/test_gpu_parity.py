@@ -3,6 +3,8 @@
 Bit-exact for plans, position ids and every cache byte; max abs error <= 1e-4 (fp32) / 2e-2 (bf16
 storage, fp32 accumulation) for attention outputs.
 """
+from dataclasses import replace
+
 import numpy as np
 import pytest
 import torch
@@ -47,11 +49,9 @@ RAGGED = [
 ]
 
 
-@pytest.mark.parametrize("case", range(len(RAGGED)))
-@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
-def test_ragged_bf16(B, case, mode):
+def _ragged_case(B, case, mode, layout=0, dtype="bf16"):
     hq, hkv, d, base, lens, ids, n_q = RAGGED[case]
-    sh = synth.Shape(hq, hkv, d, "bf16", base)
+    sh = synth.Shape(hq, hkv, d, dtype, base, layout)
     rng = np.random.Generator(np.random.PCG64([99, case]))
     row_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
     rows = int(row_start[-1])
@@ -65,9 +65,16 @@ def test_ragged_bf16(B, case, mode):
                         synth.normal_tensor(rng, (n_q, hkv, d), sh.torch_dtype),
                         synth.normal_tensor(rng, (n_q, hkv, d), sh.torch_dtype), q_pos, sum(sel), sel)
     err, n_bad = H.check_request(B, sh, store, sd, req)
-    print("ragged %d mode %d: max abs err %.3e" % (case, mode, err))
-    # the same request with the attention reading the chunks from the store (queries turned per chunk)
-    print("   gather attention: max abs err %.3e" % H.check_request_gather(B, sh, store, sd, req))
+    print("ragged %d mode %d layout %d %s: max abs err %.3e" % (case, mode, layout, dtype, err))
+    if dtype == "bf16":
+        # the same request with the attention reading the chunks from the store (queries turned per chunk)
+        print("   gather attention: max abs err %.3e" % H.check_request_gather(B, sh, store, sd, req))
+
+
+@pytest.mark.parametrize("case", range(len(RAGGED)))
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+def test_ragged_bf16(B, case, mode):
+    _ragged_case(B, case, mode)
 
 
 def test_no_documents_and_noops(B):
@@ -352,7 +359,7 @@ def _run_offline(B, sh, pc):
 
 def _check_offline(B, sh, pc, rows=None):
     out, k_rot = _run_offline(B, sh, pc)
-    o = oracle.offline_chunk_prefill(H.bits(pc.q), H.bits(pc.k), H.bits(pc.v), pc.cu, sh.rope_base, rows=rows)
+    o = oracle.offline_chunk_prefill(H.bits(pc.q), H.bits(pc.k), H.bits(pc.v), pc.cu, sh.rope_base, layout=sh.rope_layout, rows=rows)
     n_bad = H.assert_same_bits(H.bits(k_rot), o["k_rot_st"], "rotated keys K'", 1e-5)
     got = H.to_f64(out)
     if rows is not None:
@@ -452,7 +459,7 @@ def _check_sequence(B, sh, lens, n_tail, mode, seed, rows=None):
     k = synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype)
     v = synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype)
     out, k_rot = _run_sequence(B, sh, q, k, v, seg, pos)
-    o = oracle.masked_prefill(H.bits(q), H.bits(k), H.bits(v), want_seg, want_pos, sh.rope_base, rows=rows)
+    o = oracle.masked_prefill(H.bits(q), H.bits(k), H.bits(v), want_seg, want_pos, sh.rope_base, layout=sh.rope_layout, rows=rows)
     H.assert_same_bits(H.bits(k_rot), o["k_rot_st"], "keys rotated at their position ids", 1e-5)
     got = H.to_f64(out)
     if rows is not None:
@@ -497,3 +504,73 @@ def test_sequence_form_reproduces_the_offline_chunk_prefill(B):
     out_b, krot_b = _run_sequence(B, sh, pc.q, pc.k, pc.v, seg, pos)
     assert np.array_equal(H.bits(krot_a), H.bits(krot_b))
     assert np.array_equal(H.bits(out_a), H.bits(out_b))
+
+
+# ---- the half-split RoPE layout: pair m = channels (m, m + head_dim/2) -----------------------------------------------
+HALF = 1
+
+
+@pytest.mark.parametrize("case", range(len(RAGGED)))
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+def test_half_layout_ragged_bf16(B, case, mode):
+    """Assemble, append, prefix attention and gather attention on the ragged cases, keys and queries paired (m, m + d/2)."""
+    _ragged_case(B, case, mode, HALF)
+
+
+@pytest.mark.parametrize("case", [2, 3])
+def test_half_layout_ragged_fp32(B, case):
+    _ragged_case(B, case, synth.POS_REORDERED, HALF, "f32")
+
+
+def test_half_layout_batched_prefill_and_decode(B):
+    """The batched entry points (256- and 128-row workgroups chosen by the plan, the key-splitting kernel for decode) and
+    the one-launch assemble + append."""
+    for sh in (replace(synth.QWEN2_7B, rope_layout=HALF), synth.Shape(16, 2, 64, "bf16", 1e4, HALF)):
+        cfg = synth.scaled(synth.CONFIGS[3], shape=sh, store_chunks=40, chunk_len_lo=20, chunk_len_hi=90, n_requests=5,
+                           chunks_per_request=3, n_q_lo=3, n_q_hi=40)
+        store = synth.make_store(cfg)
+        sd = _store_dev(B, sh, store)
+        reqs = synth.make_requests(cfg, store)
+        print("half layout, batched prefill %s: max abs err %.3e" % (sh, _check_batched(B, cfg, store, sd, reqs)))
+        cfg = synth.scaled(cfg, n_q_lo=1, n_q_hi=1, n_requests=9)
+        reqs = synth.make_requests(cfg, store)
+        print("half layout, decode %s: max abs err %.3e" % (sh, _check_batched(B, cfg, store, sd, reqs, decode=True)))
+        r = reqs[0]
+        offsets, _ = B.tr_plan(sd, r.chunk_ids, r.pos_mode, want_pos_ids=False)
+        ck = torch.full((r.n_doc + 1, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=sh.torch_dtype, device="cuda")
+        cv = torch.full_like(ck, float("nan"))
+        B.tr_kv_assemble_append(sd, r.chunk_ids, offsets, r.pos_mode, r.k_q.cuda(), r.v_q.cuda(), torch.from_numpy(r.q_pos).cuda(), ck, cv)
+        torch.cuda.synchronize()
+        o = H.run_request_oracle(sh, store, r)
+        H.assert_same_bits(H.bits(cv.cpu()), o["v_cache_st"], "V, one launch")
+        H.assert_same_bits(H.bits(ck.cpu()), o["k_cache_st"], "K, one launch", 1e-5)
+
+
+def test_half_layout_full_size_config2(B):
+    """Configuration 2 at full size with the half-split pairing (the layout the Qwen2 weights of Sec. 4 come in)."""
+    cfg = synth.scaled(synth.CONFIGS[2], shape=replace(synth.QWEN2_7B, rope_layout=HALF))
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, cfg.shape, store)
+    req = synth.make_requests(cfg, store)[0]
+    err, n_bad = H.check_request(B, cfg.shape, store, sd, req)
+    print("half layout, config2: max abs err %.3e, K one-ulp mismatches %d; gather %.3e"
+          % (err, n_bad, H.check_request_gather(B, cfg.shape, store, sd, req)))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_half_layout_offline_and_one_pass(B, dtype):
+    lens = (70, 1, 129, 33, 64, 200, 5)
+    hq, hkv, d = (32, 8, 128) if dtype == "bf16" else (4, 4, 64)
+    sh = synth.Shape(hq, hkv, d, dtype, 5e5, HALF)
+    rng = np.random.Generator(np.random.PCG64(177))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    pc = synth.PackedChunks(synth.normal_tensor(rng, (T, hq, d), sh.torch_dtype), synth.normal_tensor(rng, (T, hkv, d), sh.torch_dtype),
+                            synth.normal_tensor(rng, (T, hkv, d), sh.torch_dtype), cu)
+    err, _ = _check_offline(B, sh, pc)
+    print("half layout, offline %s: max abs err %.3e" % (dtype, err))
+    for mode in (synth.POS_COMPOSITE, synth.POS_REORDERED):
+        print("half layout, one pass mode %d: max abs err %.3e" % (mode, _check_sequence(B, sh, (70, 1, 129, 33), 37, mode, 320 + mode)))
+    if dtype == "bf16":   # head_dim 64, GQA group 7
+        sh64 = synth.Shape(14, 2, 64, "bf16", 1e6, HALF)
+        print("half layout, one pass d=64: max abs err %.3e" % _check_sequence(B, sh64, (90, 40), 25, synth.POS_REORDERED, 330))
