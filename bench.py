@@ -419,7 +419,8 @@ def bench_sequence(torch, B, synth, acct, mfma_roof):
     q, k, v = mk(sh.n_q_heads), mk(sh.n_kv_heads), mk(sh.n_kv_heads)
     out, k_rot = torch.empty_like(q), torch.empty_like(k)
     seg_d, pos_d = torch.from_numpy(seg).cuda(), torch.from_numpy(pos).cuda()
-    run = lambda: B.tr_sequence_prefill_attn(gs, q, k, v, seg_d, pos_d, out, k_rot)
+    ws = B.workspace(B.tr_sequence_prefill_attn_workspace_size(gs, seg, T))
+    run = lambda: B.tr_sequence_prefill_attn(gs, q, k, v, seg_d, pos_d, out, k_rot, seg_start_host=seg, workspace=ws)
     t = _time_calls(torch, run, 10)
     n_doc = sum(lens)
     pairs = acct.visible_pairs_blockdiag(lens) + acct.visible_pairs_prefix(n_tail, n_doc + n_tail)

@@ -212,12 +212,21 @@ int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const void* k, c
  * tr_sequence_prefill_attn: q [T, n_q_heads, d], k, v [T, n_kv_heads, d] raw, seg_start, pos device int32 [T]
  * (0 <= seg_start[t] <= t; values outside are clamped).  k_rot_out <- R(pos[t]) k[t] (fp64, one rounding; required,
  * may alias k); token t attends rows seg_start[t] .. t of k_rot_out / v with the query rotated at pos[t];
- * out [T, n_q_heads, d].  With seg_start = chunk starts and chunk-local pos this is tr_chunk_prefill_attn. */
+ * out [T, n_q_heads, d].  With seg_start = chunk starts and chunk-local pos this is tr_chunk_prefill_attn.
+ * seg_start_host: NULL, or a HOST copy of seg_start (what tr_sequence_plan wrote), read before the call returns and
+ * used only to balance the launch: tokens whose key range is long against the chip's fair share (query tokens behind
+ * many documents) have it cut into pieces that run as separate workgroups and are merged afterwards.  The result does
+ * not depend on it beyond rounding; if it differs from the device array only speed is lost.  workspace: at least
+ * tr_sequence_prefill_attn_workspace_size() bytes (0 without the host copy, for fp32, and when nothing is cut),
+ * 256-byte aligned, else TR_ERR_WORKSPACE. */
 int tr_sequence_plan(const int32_t* chunk_lens /*host*/, int32_t n_chunks, int32_t n_tail, int32_t pos_mode, int32_t tail_start,
                      int32_t* seg_start /*host out*/, int32_t* pos /*host out*/, int64_t capacity);
+size_t tr_sequence_prefill_attn_workspace_size(const tr_shape* shape, const int32_t* seg_start_host /*host, may be NULL*/,
+                                               int64_t total_tokens);
 int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v,
-                             const int32_t* seg_start /*device*/, const int32_t* pos /*device*/, int64_t total_tokens,
-                             void* out, void* k_rot_out, void* stream);
+                             const int32_t* seg_start /*device*/, const int32_t* pos /*device*/,
+                             const int32_t* seg_start_host /*host, may be NULL*/, int64_t total_tokens,
+                             void* out, void* k_rot_out, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

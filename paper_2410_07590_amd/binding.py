@@ -27,7 +27,7 @@ EXPORTS = [
     "tr_prefill_attn_gather_workspace_size", "tr_prefill_attn_gather",
     "tr_decode_attn_workspace_size", "tr_decode_attn",
     "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
-    "tr_sequence_plan", "tr_sequence_prefill_attn",
+    "tr_sequence_plan", "tr_sequence_prefill_attn_workspace_size", "tr_sequence_prefill_attn",
 ]
 
 
@@ -60,7 +60,7 @@ def lib():
         L.tr_last_error.restype = C.c_char_p
         for name in ("tr_prefill_attn_workspace_size", "tr_prefill_attn_batched_workspace_size",
                      "tr_prefill_attn_gather_workspace_size", "tr_decode_attn_workspace_size",
-                     "tr_chunk_prefill_attn_workspace_size"):
+                     "tr_chunk_prefill_attn_workspace_size", "tr_sequence_prefill_attn_workspace_size"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -262,9 +262,20 @@ def tr_sequence_plan(chunk_lens, n_tail, pos_mode, tail_start=-1):
     return seg[:total], pos[:total]
 
 
-def tr_sequence_prefill_attn(shape, q, k, v, seg_start, pos, out, k_rot_out, stream=None):
-    _check(lib().tr_sequence_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(seg_start), _dev(pos),
-                                          C.c_int64(q.shape[0]), _dev(out), _dev(k_rot_out), _stream(stream)))
+def tr_sequence_prefill_attn_workspace_size(shape, seg_start_host, total_tokens):
+    if seg_start_host is None:
+        return 0
+    h = np.ascontiguousarray(seg_start_host, dtype=np.int32)
+    return int(lib().tr_sequence_prefill_attn_workspace_size(C.byref(shape), h.ctypes.data_as(C.c_void_p), C.c_int64(total_tokens)))
+
+
+def tr_sequence_prefill_attn(shape, q, k, v, seg_start, pos, out, k_rot_out, seg_start_host=None, workspace=None, stream=None):
+    """seg_start_host: the host array tr_sequence_plan returned (lets the library cut long key ranges into pieces)."""
+    h = None if seg_start_host is None else np.ascontiguousarray(seg_start_host, dtype=np.int32)
+    hp = C.c_void_p(0) if h is None else h.ctypes.data_as(C.c_void_p)
+    _check(lib().tr_sequence_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(seg_start), _dev(pos), hp,
+                                          C.c_int64(q.shape[0]), _dev(out), _dev(k_rot_out), _dev(workspace),
+                                          C.c_size_t(0 if workspace is None else workspace.numel()), _stream(stream)))
 
 
 def workspace(nbytes, device="cuda"):

@@ -792,8 +792,139 @@ extern "C" int tr_sequence_plan(const int32_t* chunk_lens, int32_t n_chunks, int
     });
 }
 
+namespace {
+
+constexpr int BD_SLOTS = 512;        // 128-row workgroups resident at once: two per CU
+constexpr int BD_MIN_PIECE_TILES = 16;
+
+// Work list of the block-diagonal kernel.  Without a host copy of the starts every row tile is one item per KV head.
+// With it, row tiles whose key walk is long against the chip's fair share (a query behind many documents walks all of
+// them while document tokens walk one chunk) are cut into pieces, which run as separate workgroups and are merged by
+// the combine kernel.  Fills a->seg, a->n_seg, a->items_per_head and, when comb != NULL, the merge's descriptors.
+// Returns the partial rows needed, or -1 with the error set.
+int64_t plan_blockdiag(const tr_shape* sh, const int32_t* start_host, int64_t T, int tpt, TrBlockDiagArgs* a, TrPrefixArgs* comb,
+                       int* comb_rows)
+{
+    const int64_t n_tiles = (T + tpt - 1) / tpt;
+    std::vector<int32_t> ns((size_t)n_tiles, 1), span;
+    if (start_host && sh->dtype == TR_BF16) {
+        span.resize((size_t)n_tiles);
+        double walked = 0.0; // key tiles walked by all row tiles of one KV head
+        for (int64_t tile = 0; tile < n_tiles; ++tile) {
+            const int64_t t0 = tile * tpt, t1 = std::min<int64_t>(t0 + tpt, T);
+            int64_t lo = t0;
+            for (int64_t t = t0; t < t1; ++t) lo = std::min<int64_t>(lo, std::min<int64_t>(std::max<int64_t>(start_host[t], 0), t));
+            span[(size_t)tile] = (int32_t)(t1 - lo);
+            walked += (double)((t1 - lo + KEY_TILE - 1) / KEY_TILE);
+        }
+        const double fair = walked * sh->n_kv_heads / env_int("TR_BD_SLOTS", BD_SLOTS); // key tiles per resident workgroup
+        int piece = (int)(fair / 3.0);
+        if (piece < BD_MIN_PIECE_TILES) piece = BD_MIN_PIECE_TILES;
+        piece = env_int("TR_BD_PIECE_TILES", piece);
+        if (piece < 1) piece = 1;
+        for (int64_t tile = 0; tile < n_tiles; ++tile) {
+            const int st = (span[(size_t)tile] + KEY_TILE - 1) / KEY_TILE;
+            if (st > 2 * piece) ns[(size_t)tile] = std::min(MAX_SPLIT, (st + piece - 1) / piece);
+        }
+        // runs of equal split count, at most TR_MAX_BD_SEG of them: else one run from the first to the last split tile
+        int runs = 1;
+        for (int64_t tile = 1; tile < n_tiles; ++tile) runs += ns[(size_t)tile] != ns[(size_t)tile - 1];
+        if (runs > TR_MAX_BD_SEG) {
+            int64_t first = -1, last = -1;
+            int32_t most = 1;
+            for (int64_t tile = 0; tile < n_tiles; ++tile)
+                if (ns[(size_t)tile] > 1) { if (first < 0) first = tile; last = tile; most = std::max(most, ns[(size_t)tile]); }
+            for (int64_t tile = first; tile <= last; ++tile) ns[(size_t)tile] = most;
+        }
+    }
+    int n_seg = 0;
+    int64_t items = 0, ws_rows = 0;
+    for (int64_t hi = n_tiles - 1; hi >= 0;) {
+        int64_t lo = hi;
+        while (lo > 0 && ns[(size_t)lo - 1] == ns[(size_t)hi]) --lo;
+        TrBdSeg& g = a->seg[n_seg++];
+        g.tile_hi = (int32_t)hi;
+        g.n_tiles = (int32_t)(hi - lo + 1);
+        g.n_split = ns[(size_t)hi];
+        g.item0 = (int32_t)items;
+        g.tok0 = (int32_t)(lo * tpt);
+        g.n_tok = (int32_t)(std::min<int64_t>((hi + 1) * tpt, T) - lo * tpt);
+        g.split_len = 0;
+        g.ws_row0 = 0;
+        if (g.n_split > 1) {
+            int32_t longest = 0;
+            for (int64_t tile = lo; tile <= hi; ++tile) longest = std::max(longest, span[(size_t)tile]);
+            const int64_t len = (longest + g.n_split - 1) / g.n_split;
+            g.split_len = (int32_t)(((len + KEY_TILE - 1) / KEY_TILE) * KEY_TILE);
+            g.ws_row0 = (int32_t)ws_rows;
+            ws_rows += (int64_t)g.n_split * g.n_tok * sh->n_q_heads;
+        }
+        items += (int64_t)g.n_tiles * g.n_split;
+        hi = lo - 1;
+    }
+    if (items * sh->n_kv_heads > ROW_LIMIT || ws_rows > ROW_LIMIT) {
+        tr_fail(TR_ERR_UNSUPPORTED, "the sequence needs 2^31 work items or partial rows, or more");
+        return -1;
+    }
+    a->n_seg = n_seg;
+    a->items_per_head = (int32_t)items;
+    if (comb) {
+        // the merge walks the tokens from the first split segment to the last; segments are in descending token order
+        memset(comb, 0, sizeof *comb);
+        int first = -1, last = -1;
+        for (int i = 0; i < n_seg; ++i)
+            if (a->seg[i].n_split > 1) { if (first < 0) first = i; last = i; }
+        *comb_rows = 0;
+        if (first >= 0) {
+            int n = 0;
+            int64_t toks = 0;
+            for (int i = last; i >= first; --i) { // ascending tokens
+                const TrBdSeg& g = a->seg[i];
+                TrSeqDesc& d = comb->seq[n++];
+                d.q_row0 = g.tok0;
+                d.n_q = g.n_tok;
+                d.n_split = g.n_split;
+                d.ws_row0 = g.ws_row0;
+                toks += g.n_tok;
+            }
+            comb->n_seq = n;
+            comb->n_q_heads = sh->n_q_heads;
+            comb->n_kv_heads = sh->n_kv_heads;
+            comb->group = sh->n_q_heads / sh->n_kv_heads;
+            *comb_rows = (int)(toks * sh->n_q_heads);
+        }
+    }
+    return ws_rows;
+}
+
+size_t blockdiag_ws_bytes(const tr_shape* sh, int64_t ws_rows)
+{
+    return ws_rows > 0 ? tr_align256((size_t)ws_rows * sh->head_dim * 2) + tr_align256((size_t)ws_rows * 8) : 0;
+}
+
+int sequence_tok_per_tile(const tr_shape* sh, int* wg_rows)
+{
+    *wg_rows = env_int("TR_WG_ROWS", 0) == 256 ? 256 : 128;
+    return *wg_rows / (sh->n_q_heads / sh->n_kv_heads);
+}
+
+} // namespace
+
+extern "C" size_t tr_sequence_prefill_attn_workspace_size(const tr_shape* shape, const int32_t* seg_start_host, int64_t total_tokens)
+{
+    return tr_guard_size([&]() -> size_t {
+    if (tr_check_shape(shape) || total_tokens <= 0 || total_tokens > ROW_LIMIT || !seg_start_host) return 0;
+    int wg_rows;
+    const int tpt = sequence_tok_per_tile(shape, &wg_rows);
+    TrBlockDiagArgs a;
+    const int64_t rows = plan_blockdiag(shape, seg_start_host, total_tokens, tpt, &a, nullptr, nullptr);
+    return rows > 0 ? blockdiag_ws_bytes(shape, rows) : 0;
+    });
+}
+
 extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* seg_start,
-                                        const int32_t* pos, int64_t total_tokens, void* out, void* k_rot_out, void* stream)
+                                        const int32_t* pos, const int32_t* seg_start_host, int64_t total_tokens, void* out,
+                                        void* k_rot_out, void* workspace, size_t workspace_bytes, void* stream)
 {
     return tr_guard_int([&]() -> int {
     tr_clear_error();
@@ -805,6 +936,24 @@ extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, co
     if (!q || !k || !v || !seg_start || !pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_sequence_prefill_attn: NULL pointer");
     if (!k_rot_out) return tr_fail(TR_ERR_INVALID_ARG, "k_rot_out is required (it may alias k)");
     hipStream_t s = (hipStream_t)stream;
+    TrBlockDiagArgs a;
+    memset(&a, 0, sizeof a);
+    TrPrefixArgs comb;
+    int comb_rows = 0, wg_rows;
+    a.tok_per_tile = sequence_tok_per_tile(shape, &wg_rows);
+    const int64_t ws_rows = plan_blockdiag(shape, seg_start_host, total_tokens, a.tok_per_tile, &a, &comb, &comb_rows);
+    if (ws_rows < 0) return TR_ERR_UNSUPPORTED;
+    const size_t need = blockdiag_ws_bytes(shape, ws_rows);
+    if (need > 0) {
+        if (!workspace) return tr_fail(TR_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+        if (((uintptr_t)workspace & 255) != 0) return tr_fail(TR_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+        if (workspace_bytes < need) return tr_fail(TR_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+        a.ws_o = (_Float16*)workspace;
+        a.ws_ml = (float*)((char*)workspace + tr_align256((size_t)ws_rows * shape->head_dim * 2));
+        comb.ws_o = a.ws_o;
+        comb.ws_ml = a.ws_ml;
+        comb.out = out;
+    }
     // keys rotated at their position ids, fp64, one rounding (the arithmetic of the query append), values untouched
     std::vector<TrAppendDesc> d(1);
     d[0].q_row0 = 0;
@@ -812,8 +961,6 @@ extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, co
     d[0].dst_row0 = 0;
     rc = launch_append(shape, k, nullptr, pos, d, k_rot_out, nullptr, s);
     if (rc) return rc;
-    TrBlockDiagArgs a;
-    memset(&a, 0, sizeof a);
     tr_fill_theta(shape, a.theta);
     for (int m = 0; m < 64; ++m) a.theta_rev[m] = a.theta[m] / 6.283185307179586476925;
     a.q = q;
@@ -827,13 +974,11 @@ extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, co
     a.n_kv_heads = shape->n_kv_heads;
     a.group = shape->n_q_heads / shape->n_kv_heads;
     a.rope_half = tr_rope_half(shape);
-    const int wg_rows = env_int("TR_WG_ROWS", 0) == 256 ? 256 : 128;
-    a.tok_per_tile = wg_rows / a.group;
     a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);
     a.scale = (float)(1.0 / sqrt((double)shape->head_dim));
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)shape->head_dim));
     if (shape->dtype == TR_F32) return tr_launch_blockdiag_attn_f32(a, shape->head_dim, s);
-    return tr_launch_blockdiag_attn(a, shape->head_dim, wg_rows, s);
+    return tr_launch_blockdiag_attn(a, comb_rows > 0 ? &comb : nullptr, comb_rows, shape->head_dim, wg_rows, s);
     });
 }
 
@@ -928,7 +1073,8 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
     a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);
     a.scale = (float)(1.0 / sqrt((double)shape->head_dim));
     a.scale_log2e = (float)(1.4426950408889634074 / sqrt((double)shape->head_dim));
+    if (plan_blockdiag(shape, nullptr, total_tokens, a.tok_per_tile, &a, nullptr, nullptr) < 0) return TR_ERR_UNSUPPORTED;
     if (shape->dtype == TR_F32) return tr_launch_blockdiag_attn_f32(a, shape->head_dim, s);
-    return tr_launch_blockdiag_attn(a, shape->head_dim, wg_rows, s);
+    return tr_launch_blockdiag_attn(a, nullptr, 0, shape->head_dim, wg_rows, s);
     });
 }

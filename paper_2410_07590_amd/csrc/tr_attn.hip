@@ -1027,12 +1027,19 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
 {
     extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
     LDS_AS char* smem = (LDS_AS char*)smem_raw;
-    const int n_items = a.n_tiles * a.n_kv_heads;
-    const int item = xcd_remap(blockIdx.x, n_items);
+    const int item = xcd_remap(blockIdx.x, a.items_per_head * a.n_kv_heads);
+    const int kvh = item / a.items_per_head;
+    const int j = item % a.items_per_head;
+    int slo = 0, shi = a.n_seg - 1;
+    while (slo < shi) {
+        const int mid = (slo + shi + 1) >> 1;
+        if (a.seg[mid].item0 <= j) slo = mid; else shi = mid - 1;
+    }
+    const TrBdSeg sg = a.seg[slo];
     // last row tiles first: under a causal mask they walk the most keys (a query behind the documents walks all of
     // them), so they must not be the ones that start last
-    const int tile = a.n_tiles - 1 - item % a.n_tiles;
-    const int kvh = item / a.n_tiles;
+    const int tile = sg.tile_hi - (j - sg.item0) / sg.n_split;
+    const int split = (j - sg.item0) % sg.n_split;
     const int g = a.group, tpt = a.tok_per_tile;
     const int T = a.total_tokens;
 
@@ -1067,7 +1074,14 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     }
     lo_first = wave_min_i(lo_first);
     lo_last = wave_max_i(lo_last);
-    const Walk w = make_walk(lo_first, t_last + 1, T - 1, a.n_kv_heads, kvh, D);
+    // this item's piece of the walk [lo_first, t_last]: pieces of split_len keys, the last one open-ended
+    int kb = lo_first, ke = t_last + 1;
+    if (sg.n_split > 1) {
+        const int64_t kb64 = (int64_t)lo_first + (int64_t)split * sg.split_len;
+        kb = (int)(kb64 < ke ? kb64 : ke);
+        if (split + 1 < sg.n_split && (int64_t)kb + sg.split_len < ke) ke = kb + sg.split_len;
+    }
+    const Walk w = make_walk(kb, ke, T - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
     prologue<D, NW, NS, HALF>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
@@ -1086,7 +1100,14 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     const float l_tot = acc.l + __shfl_xor(acc.l, 32);
     __builtin_amdgcn_s_barrier();
     LDS_AS char* wave_buf = smem + wave * (32 * (64 * 4 + 16));
-    store_rows<D, false>(acc, l_tot, rc.valid, (int64_t)rc.orow, a.out, wave_buf, lane);
+    if (sg.n_split == 1) {
+        store_rows<D, false>(acc, l_tot, rc.valid, (int64_t)rc.orow, a.out, wave_buf, lane);
+    } else { // the layout the merge kernel reads: [split][KV head][token of the segment x group]
+        const int64_t rows_s = (int64_t)sg.n_tok * g;
+        const int64_t prow = (int64_t)sg.ws_row0 + ((int64_t)split * a.n_kv_heads + kvh) * rows_s + (int64_t)(t - sg.tok0) * g + rl % g;
+        store_rows<D, true>(acc, l_tot, rc.valid, prow, a.ws_o, wave_buf, lane);
+        if (rc.valid && lane < 32) *(float2*)(a.ws_ml + prow * 2) = make_float2(l_tot > 0.0f ? acc.mref : -INFINITY, l_tot);
+    }
 }
 
 template <int D, int NW, int NS> constexpr int smem_bytes()
@@ -1154,7 +1175,7 @@ int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
         TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.n_kv_heads), dim3(64 * NW), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(a.items_per_head * a.n_kv_heads), dim3(64 * NW), lds, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;
 }
@@ -1210,8 +1231,17 @@ int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_arg
     return TR_OK;
 }
 
-int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s)
+int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, const TrPrefixArgs* combine, int combine_rows, int head_dim, int wg_rows,
+                             hipStream_t s)
 {
     if (a.total_tokens <= 0) return TR_OK;
-    return a.rope_half ? blockdiag_dispatch<true>(a, head_dim, wg_rows, s) : blockdiag_dispatch<false>(a, head_dim, wg_rows, s);
+    const int rc = a.rope_half ? blockdiag_dispatch<true>(a, head_dim, wg_rows, s) : blockdiag_dispatch<false>(a, head_dim, wg_rows, s);
+    if (rc) return rc;
+    if (combine && combine_rows > 0) {
+        const int blocks = (combine_rows + 7) / 8;
+        if (head_dim == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3(blocks), dim3(256), 0, s, *combine, combine_rows);
+        else hipLaunchKernelGGL(combine_kernel<64>, dim3(blocks), dim3(256), 0, s, *combine, combine_rows);
+        TR_HIP(hipGetLastError());
+    }
+    return TR_OK;
 }

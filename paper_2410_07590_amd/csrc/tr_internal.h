@@ -167,6 +167,19 @@ struct TrGatherArgs {
     TrGatherSeg seg[TR_MAX_GATHER_SEG];
 };
 
+// A run of consecutive row tiles of the block-diagonal kernel that share one split count.  Items of a KV head are
+// numbered segment by segment, tiles in DESCENDING order inside a segment, the splits of a tile next to each other.
+struct TrBdSeg {
+    int32_t tile_hi;   // last (highest) row tile of the segment: the first one issued
+    int32_t n_tiles;
+    int32_t n_split;   // pieces the key walk of each tile is cut into (>= 1)
+    int32_t split_len; // keys per piece, a multiple of 64; the last piece runs to the end of the walk
+    int32_t item0;     // first item of the segment inside a KV head's item list
+    int32_t ws_row0;   // first partial row of the segment (n_split > 1)
+    int32_t tok0;      // first token of the segment
+    int32_t n_tok;     // tokens in the segment
+};
+#define TR_MAX_BD_SEG 64
 struct TrBlockDiagArgs {
     const void* q;
     const void* k; // rotated keys K'
@@ -183,9 +196,14 @@ struct TrBlockDiagArgs {
     float scale_log2e;
     float scale;
     int32_t rope_half;
+    int32_t n_seg;
+    int32_t items_per_head;
     int32_t pad_;
+    _Float16* ws_o; // partial outputs and statistics of split tiles, laid out as in TrPrefixArgs
+    float* ws_ml;
     double theta_rev[64];
     double theta[64];
+    TrBdSeg seg[TR_MAX_BD_SEG];
 };
 
 static_assert(sizeof(TrAssembleArgs) <= 4096 && sizeof(TrAppendArgs) <= 4096 && sizeof(TrPrefixArgs) <= 4096 &&
@@ -201,6 +219,8 @@ int tr_launch_rope_table(double* table, int n_pos, int half_dim, const double* t
 int tr_launch_rope_rows(const void* k, void* k_rot, const int32_t* cu, int n_chunks, int max_chunk_len, int32_t* tok_start,
                         const double* table, int table_rows, int64_t total_tokens, const tr_shape* shape, hipStream_t s);
 static inline int tr_rope_half(const tr_shape* s) { return s->rope_layout == TR_ROPE_HALF ? 1 : 0; }
-int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipStream_t s);
+// combine: NULL, or the arguments of the merge over the split tiles' tokens (combine_rows = tokens x query heads)
+int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, const TrPrefixArgs* combine, int combine_rows, int head_dim, int wg_rows,
+                             hipStream_t s);
 int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_args, int head_dim, hipStream_t s);
 int tr_launch_blockdiag_attn_f32(const TrBlockDiagArgs& a, int head_dim, hipStream_t s);

@@ -305,7 +305,8 @@ def test_sequence_plan_is_bit_exact_against_the_oracle(L, mode):
 def test_sequence_prefill_validation(L):
     sh = _shape()
     call = lambda **kw: L.tr_sequence_prefill_attn(C.byref(kw.get("shape", sh)), kw.get("q", FAKE), FAKE, FAKE, kw.get("seg", FAKE),
-                                                   kw.get("pos", FAKE), C.c_int64(kw.get("T", 100)), FAKE, kw.get("krot", FAKE2), None)
+                                                   kw.get("pos", FAKE), kw.get("seg_host", None), C.c_int64(kw.get("T", 100)), FAKE,
+                                                   kw.get("krot", FAKE2), kw.get("ws", None), C.c_size_t(kw.get("ws_bytes", 0)), None)
     assert call(q=None) == B.TR_ERR_INVALID_ARG
     assert call(seg=None) == B.TR_ERR_INVALID_ARG
     assert call(pos=None) == B.TR_ERR_INVALID_ARG
@@ -313,6 +314,18 @@ def test_sequence_prefill_validation(L):
     assert call(T=-1) == B.TR_ERR_INVALID_ARG
     assert call(shape=_shape(d=96)) == B.TR_ERR_SHAPE
     assert call(T=0) == B.TR_OK
+    # with the host copy of the starts, 256 tokens that each attend 40000 rows are cut into pieces: a workspace is needed
+    T = 40000 + 256
+    seg, seg_p = _i32(np.concatenate([np.arange(40000) // 1000 * 1000, np.zeros(256)]))
+    L.tr_sequence_prefill_attn_workspace_size.restype = C.c_size_t
+    size = L.tr_sequence_prefill_attn_workspace_size(C.byref(sh), seg_p, C.c_int64(T))
+    n_split = size // (256 * sh.n_q_heads * (sh.head_dim * 2 + 8))
+    assert 2 <= n_split <= 32 and size % 256 == 0, size
+    assert L.tr_sequence_prefill_attn_workspace_size(C.byref(sh), None, C.c_int64(T)) == 0
+    assert L.tr_sequence_prefill_attn_workspace_size(C.byref(sh), seg_p, C.c_int64(40000)) == 0    # chunks only: nothing is cut
+    assert call(T=T, seg_host=seg_p) == B.TR_ERR_WORKSPACE
+    assert call(T=T, seg_host=seg_p, ws=FAKE, ws_bytes=size - 256) == B.TR_ERR_WORKSPACE
+    assert call(T=T, seg_host=seg_p, ws=C.c_void_p(0x1010), ws_bytes=size) == B.TR_ERR_WORKSPACE   # not 256-byte aligned
 
 
 def test_gather_attention_validation(L):

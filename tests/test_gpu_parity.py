@@ -440,16 +440,19 @@ def test_offline_store_feeds_online_path(B):
 
 
 # ---- one pass over [chunks, query/answer] with the masks and position ids of inference (Sec. 3.3) ---------------
-def _run_sequence(B, sh, q, k, v, seg, pos):
+def _run_sequence(B, sh, q, k, v, seg, pos, host_copy=True):
+    """host_copy: hand the library the host array of the starts, so that it may cut long key ranges into pieces."""
     gs = H.gpu_shape(B, sh)
     out = torch.full(q.shape, float("nan"), dtype=sh.torch_dtype, device="cuda")
     k_rot = torch.full(k.shape, float("nan"), dtype=sh.torch_dtype, device="cuda")
-    B.tr_sequence_prefill_attn(gs, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(seg).cuda(), torch.from_numpy(pos).cuda(), out, k_rot)
+    ws = B.workspace(B.tr_sequence_prefill_attn_workspace_size(gs, seg, seg.size)) if host_copy else None
+    B.tr_sequence_prefill_attn(gs, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(seg).cuda(), torch.from_numpy(pos).cuda(), out, k_rot,
+                               seg_start_host=seg if host_copy else None, workspace=ws)
     torch.cuda.synchronize()
     return out.cpu(), k_rot.cpu()
 
 
-def _check_sequence(B, sh, lens, n_tail, mode, seed, rows=None):
+def _check_sequence(B, sh, lens, n_tail, mode, seed, rows=None, host_copy=True):
     rng = np.random.Generator(np.random.PCG64(seed))
     seg, pos = B.tr_sequence_plan(lens, n_tail, mode)
     want_seg, want_pos = oracle.sequence_plan(lens, n_tail, mode)
@@ -458,7 +461,7 @@ def _check_sequence(B, sh, lens, n_tail, mode, seed, rows=None):
     q = synth.normal_tensor(rng, (T, sh.n_q_heads, sh.head_dim), sh.torch_dtype)
     k = synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype)
     v = synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype)
-    out, k_rot = _run_sequence(B, sh, q, k, v, seg, pos)
+    out, k_rot = _run_sequence(B, sh, q, k, v, seg, pos, host_copy)
     o = oracle.masked_prefill(H.bits(q), H.bits(k), H.bits(v), want_seg, want_pos, sh.rope_base, layout=sh.rope_layout, rows=rows)
     H.assert_same_bits(H.bits(k_rot), o["k_rot_st"], "keys rotated at their position ids", 1e-5)
     got = H.to_f64(out)
@@ -487,6 +490,32 @@ def test_sequence_one_pass_config2_shape_sampled(B):
     rows = np.unique(np.concatenate([np.arange(0, T, 257), np.arange(T - 64, T, 9), [511, 512, T - 1]])).astype(np.int32)
     err = _check_sequence(B, synth.QWEN2_7B, (512,) * 8, 64, synth.POS_REORDERED, 310, rows)
     print("one-pass sequence, 8 x 512 + 64: max abs err %.3e on %d sampled tokens" % (err, rows.size))
+
+
+def test_sequence_one_pass_without_the_host_copy(B):
+    """No host copy of the starts: nothing is cut, no workspace, same result."""
+    rows = np.unique(np.concatenate([np.arange(0, 2112, 131), np.arange(2048, 2112, 7)])).astype(np.int32)
+    err = _check_sequence(B, synth.QWEN2_7B, (512,) * 4, 64, synth.POS_REORDERED, 312, rows, host_copy=False)
+    print("one-pass sequence, no host copy: max abs err %.3e" % err)
+
+
+@pytest.mark.parametrize("piece", [1, 3])
+def test_sequence_one_pass_cut_key_ranges(B, monkeypatch, piece):
+    """Pieces of one and three key tiles forced onto short sequences: every row tile that walks more than two pieces is
+    cut, pieces that hold no visible key for some rows, the merge over tail and document tokens; chunk lengths that
+    alternate so that the split count changes more often than the launch can describe (one coarse run instead); the
+    half-split layout; a GQA group that does not divide the row tile."""
+    monkeypatch.setenv("TR_BD_PIECE_TILES", str(piece))
+    cases = [(synth.QWEN2_7B, (70, 1, 129, 33, 64), 37), (synth.LLAMA3_8B, (300, 5, 260), 130),
+             (synth.LLAMA3_8B, (200, 40) * 36, 50), (synth.Shape(14, 2, 64, "bf16", 1e6, 1), (250, 90), 25),
+             (synth.LLAMA3_8B, (), 700)]
+    worst = 0.0
+    for i, (sh, lens, n_tail) in enumerate(cases):
+        seg, _ = B.tr_sequence_plan(lens, n_tail, synth.POS_REORDERED)
+        assert piece > 1 or B.tr_sequence_prefill_attn_workspace_size(H.gpu_shape(B, sh), seg, seg.size) > 0   # this case is cut
+        for mode in (synth.POS_COMPOSITE, synth.POS_REORDERED):
+            worst = max(worst, _check_sequence(B, sh, lens, n_tail, mode, 340 + i))
+    print("one-pass sequence, pieces of %d key tiles: max abs err %.3e" % (piece, worst))
 
 
 def test_sequence_form_reproduces_the_offline_chunk_prefill(B):
