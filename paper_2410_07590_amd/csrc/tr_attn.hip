@@ -39,6 +39,7 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int KT = 64;               // keys per tile
 constexpr float RESCALE_SLACK = 8.f; // log2 units a tile maximum may exceed the reference before a rescale
+constexpr int K_PREFETCH = 2;        // k-steps the K operand reads run ahead of the score products
 constexpr float REREF_BELOW = -32.f; // a row's first visible tile re-references when its maximum is below this
 
 template <int D> struct Geo {
@@ -253,13 +254,23 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* krows, const b
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[kb][e] = -acc.mref;
+    // operand reads run K_PREFETCH k-steps ahead of the products that use them (the compiler, left alone, reads one
+    // step ahead and waits out the full LDS latency before every pair of products)
+    constexpr int PD = K_PREFETCH, STEPS = D / 16;
+    bf16x8 a[PD][KB];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) {
+    for (int ks = 0; ks < PD; ++ks)
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const bf16x8 a = *(LDS_AS const bf16x8*)(krows + koff[ks] + kb * 32 * D * 2);
-            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+        for (int kb = 0; kb < KB; ++kb) a[ks][kb] = *(LDS_AS const bf16x8*)(krows + koff[ks] + kb * 32 * D * 2);
+#pragma unroll
+    for (int ks = 0; ks < STEPS; ++ks) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % PD][kb], qf[ks], s[kb], 0, 0, 0);
+        if (ks + PD < STEPS) {
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) a[ks % PD][kb] = *(LDS_AS const bf16x8*)(krows + koff[ks + PD] + kb * 32 * D * 2);
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
     // accumulator element e of block kb is key kt + 32 kb + 8 (e >> 2) + 4 h + (e & 3), query column c
     if (need_mask) { // workgroup-uniform: only tiles that straddle a mask edge
