@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <algorithm>
+#include <functional>
 #include <new>
 
 // ---- errors ---------------------------------------------------------------------------------------------------
@@ -422,6 +423,44 @@ int pick_wg_rows(const tr_shape* sh, int64_t max_rows_per_kv_head)
     return max_rows_per_kv_head >= 512 ? 256 : 128;
 }
 
+// How a request's keys are cut: n_split pieces of split_len keys (a multiple of the key tile).
+struct SplitPlan { int n_split; int64_t split_len; };
+
+SplitPlan cut_keys(int64_t kv_len, int want, int min_split_keys, int key_tile)
+{
+    int n_split = want;
+    const int64_t max_split = (kv_len + min_split_keys - 1) / min_split_keys;
+    if (n_split > max_split) n_split = (int)max_split;
+    if (n_split > MAX_SPLIT) n_split = MAX_SPLIT;
+    if (n_split < 1) n_split = 1;
+    int64_t split_len = (kv_len + n_split - 1) / n_split;
+    split_len = ((split_len + key_tile - 1) / key_tile) * key_tile;
+    n_split = (int)((kv_len + split_len - 1) / split_len);
+    return {n_split, split_len};
+}
+
+// Finishing time, in key-tile steps, of a launch whose items (in launch order) walk item_tiles[i] key tiles each.
+// Blocks are dealt round-robin to the 8 XCDs and the kernels map each XCD to one contiguous range of items, so
+// every XCD works through its own range on its own slots; a workgroup costs FIXED steps besides its tiles.
+double launch_makespan(const std::vector<int>& item_tiles, int slots_per_xcd)
+{
+    const double FIXED = 3.0;
+    const size_t n = item_tiles.size(), q = n / 8, r = n % 8;
+    double worst = 0.0;
+    std::vector<double> slot;
+    for (size_t x = 0; x < 8; ++x) {
+        const size_t lo = x * q + std::min(x, r), hi = lo + q + (x < r ? 1 : 0);
+        slot.assign((size_t)slots_per_xcd, 0.0);
+        for (size_t i = lo; i < hi; ++i) { // the next block goes to the slot that frees first
+            std::pop_heap(slot.begin(), slot.end(), std::greater<double>());
+            slot.back() += FIXED + item_tiles[i];
+            std::push_heap(slot.begin(), slot.end(), std::greater<double>());
+        }
+        for (double t : slot) worst = std::max(worst, t);
+    }
+    return worst;
+}
+
 // Fills the per-request descriptors of one launch (requests [r0, r1)); returns the partial rows it needs.
 int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t r0, size_t r1, TrPrefixArgs* a,
                     bool* any_split, int* total_tokens, int* wg_rows_out)
@@ -438,20 +477,55 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
     int want_split = 1;
     if (sh->dtype == TR_BF16 && base_items > 0 && base_items < target) want_split = (int)((target + base_items - 1) / base_items);
     if (want_split > MAX_SPLIT) want_split = MAX_SPLIT;
+    const int key_tile = wg_rows == 32 ? 2 * KEY_TILE : KEY_TILE; // the short-query kernel walks 128 keys a step
+    std::vector<SplitPlan> cut(r1 - r0);
+    for (size_t r = r0; r < r1; ++r) cut[r - r0] = cut_keys(reqs[r].kv_len, want_split, min_split_keys, key_tile);
+    // A batch of requests of different lengths: one split count for all leaves workgroups of very different lengths,
+    // and how the launch then packs onto the chip swings by tens of percent with the count.  Instead every request is
+    // cut into pieces of about one common length, and that length is chosen by playing the launch through
+    // (launch_makespan) for a range of candidates, with the traffic of the partial results priced in.
+    if (want_split > 1 && r1 - r0 > 1 && wg_rows != 32 && !getenv("TR_TARGET_ITEMS")) {
+        double walked = 0.0; // keys walked by all row tiles of all KV heads
+        for (size_t r = r0; r < r1; ++r) walked += (double)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads * (double)reqs[r].kv_len;
+        const int slots_per_xcd = wg_rows == 256 ? 32 : 64;
+        const double STEP_US = 2.0, PARTIAL_BYTES_PER_US = 2.0e6; // a key-tile step; write + read of partials at ~4 TB/s
+        double best = 1e300;
+        std::vector<SplitPlan> cand(r1 - r0);
+        std::vector<int> item_tiles;
+        for (int c = 0; c < 24; ++c) {
+            const double n_items = 8.0 * slots_per_xcd * 0.75 * pow(4.0 / 0.75, c / 23.0); // 0.75x .. 4x the resident workgroups
+            const double keys_per_item = walked / n_items;
+            item_tiles.clear();
+            double partial_bytes = 0.0;
+            for (size_t r = r0; r < r1; ++r) {
+                const ReqGeom& q = reqs[r];
+                if (q.n_q == 0) continue;
+                const SplitPlan sp = cut_keys(q.kv_len, (int)((double)q.kv_len / keys_per_item + 0.5), min_split_keys, key_tile);
+                cand[r - r0] = sp;
+                const int n_tiles = (q.n_q + tpt - 1) / tpt;
+                const int64_t n_doc = q.kv_len - q.n_q;
+                for (int kvh = 0; kvh < sh->n_kv_heads; ++kvh)
+                    for (int sp_i = 0; sp_i < sp.n_split; ++sp_i)
+                        for (int tile = 0; tile < n_tiles; ++tile) { // the kernel's item order
+                            const int64_t sb = (int64_t)sp_i * sp.split_len;
+                            const int64_t last_tok = std::min<int64_t>((int64_t)(tile + 1) * tpt, q.n_q) - 1;
+                            const int64_t se = std::min<int64_t>(std::min<int64_t>(sb + sp.split_len, q.kv_len), n_doc + last_tok + 1);
+                            item_tiles.push_back(se > sb ? (int)((se - sb + key_tile - 1) / key_tile) : 0);
+                        }
+                if (sp.n_split > 1) partial_bytes += (double)sp.n_split * q.n_q * sh->n_q_heads * (sh->head_dim * 2 + 8);
+            }
+            const double cost = launch_makespan(item_tiles, slots_per_xcd) * STEP_US + 2.0 * partial_bytes / PARTIAL_BYTES_PER_US;
+            if (cost < best) { best = cost; cut = cand; }
+        }
+    }
     int items = 0, n = 0, toks = 0;
     int64_t ws_rows = 0;
     bool any = false;
     for (size_t r = r0; r < r1; ++r) {
         const ReqGeom& q = reqs[r];
         if (q.n_q == 0) continue;
-        int n_split = want_split;
-        const int64_t max_split = (q.kv_len + min_split_keys - 1) / min_split_keys;
-        if (n_split > max_split) n_split = (int)max_split;
-        if (n_split < 1) n_split = 1;
-        const int key_tile = wg_rows == 32 ? 2 * KEY_TILE : KEY_TILE; // the short-query kernel walks 128 keys a step
-        int64_t split_len = (q.kv_len + n_split - 1) / n_split;
-        split_len = ((split_len + key_tile - 1) / key_tile) * key_tile;
-        n_split = (int)((q.kv_len + split_len - 1) / split_len);
+        const int n_split = cut[r - r0].n_split;
+        const int64_t split_len = cut[r - r0].split_len;
         if (a) {
             TrSeqDesc& d = a->seq[n];
             d.q_row0 = q.q_row0;
