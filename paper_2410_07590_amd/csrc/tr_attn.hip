@@ -110,9 +110,11 @@ __device__ __forceinline__ void load_q_raw(const __bf16* __restrict__ q, const R
     for (int ks = 0; ks < D / 16; ++ks) raw[ks] = *(const u32x4*)(qrow + 16 * ks);
 }
 
-__device__ __forceinline__ void rot_pair(uint32_t w, float cn, float sn, float sl2e, bool valid, bf16x8& f, int p)
+// cn, sn: cosine and sine of the pair's angle, already multiplied by the score scale.  Rows that do not exist are
+// rotated like any other (they hold row 0's values and are never stored).
+__device__ __forceinline__ void rot_pair(uint32_t w, float cn, float sn, bf16x8& f, int p)
 {
-    const float xa = valid ? bf_lo(w) * sl2e : 0.0f, xb = valid ? bf_hi(w) * sl2e : 0.0f;
+    const float xa = bf_lo(w), xb = bf_hi(w);
     f[2 * p] = (__bf16)(xa * cn - xb * sn);
     f[2 * p + 1] = (__bf16)(xb * cn + xa * sn);
 }
@@ -122,7 +124,8 @@ __device__ __forceinline__ void rot_pair(uint32_t w, float cn, float sn, float s
 // one token slot (two for D = 64) per step.  pos_lane: position id of slot (lane & 7).
 // Table layout: slot j, pair m at byte j * 4 D + (((m >> 1) ^ 2 j) * 16) + (m & 1) * 8.
 template <int D>
-__device__ __forceinline__ void build_rot_table(LDS_AS char* tab, double th /* theta_rev[lane % (D/2)] */, int lane, int pos_lane)
+__device__ __forceinline__ void build_rot_table(LDS_AS char* tab, double th /* theta_rev[lane % (D/2)] */, int lane, int pos_lane,
+                                                float sl2e /* log2(e) / sqrt(d): folded into the table */)
 {
     constexpr int PAIRS = D / 2, LPS = 64 / PAIRS;
     const int m = lane % PAIRS;
@@ -133,15 +136,15 @@ __device__ __forceinline__ void build_rot_table(LDS_AS char* tab, double th /* t
         rev -= rint(rev);
         const float x = (float)rev;
         f32x2 cs;
-        cs[0] = __builtin_amdgcn_cosf(x);
-        cs[1] = __builtin_amdgcn_sinf(x);
+        cs[0] = __builtin_amdgcn_cosf(x) * sl2e;
+        cs[1] = __builtin_amdgcn_sinf(x) * sl2e;
         *(LDS_AS f32x2*)(tab + j * (4 * D) + (((m >> 1) ^ (2 * j)) * 16) + (m & 1) * 8) = cs;
     }
 }
 
 template <int D>
 __device__ __forceinline__ void rotate_q_shared(const u32x4 (&raw)[D / 16], LDS_AS const char* tab, int slot, int h,
-                                                bool valid, float sl2e, bf16x8 (&qf)[D / 16])
+                                                bf16x8 (&qf)[D / 16])
 {
     LDS_AS const char* row = tab + slot * (4 * D);
 #pragma unroll
@@ -151,10 +154,10 @@ __device__ __forceinline__ void rotate_q_shared(const u32x4 (&raw)[D / 16], LDS_
         const f32x4 cs0 = *(LDS_AS const f32x4*)(row + ch * 16);
         const f32x4 cs1 = *(LDS_AS const f32x4*)(row + ch * 16 + 16);
         bf16x8 f;
-        rot_pair(raw[ks][0], cs0[0], cs0[1], sl2e, valid, f, 0);
-        rot_pair(raw[ks][1], cs0[2], cs0[3], sl2e, valid, f, 1);
-        rot_pair(raw[ks][2], cs1[0], cs1[1], sl2e, valid, f, 2);
-        rot_pair(raw[ks][3], cs1[2], cs1[3], sl2e, valid, f, 3);
+        rot_pair(raw[ks][0], cs0[0], cs0[1], f, 0);
+        rot_pair(raw[ks][1], cs0[2], cs0[3], f, 1);
+        rot_pair(raw[ks][2], cs1[0], cs1[1], f, 2);
+        rot_pair(raw[ks][3], cs1[2], cs1[3], f, 3);
         qf[ks] = f;
     }
 }
@@ -164,14 +167,14 @@ __device__ __forceinline__ void rotate_q_shared(const u32x4 (&raw)[D / 16], LDS_
 // row, sw: twice the slot (the swizzle of its 16-byte chunks).
 template <int D>
 __device__ __forceinline__ void rot_frag_half(const u32x4& lo, const u32x4& hi, LDS_AS const char* row, int ks, int h, int sw,
-                                              bool valid, float sl2e, bf16x8& flo, bf16x8& fhi)
+                                              bf16x8& flo, bf16x8& fhi)
 {
 #pragma unroll
     for (int q = 0; q < 4; ++q) { // two pairs (one 16-byte table chunk) at a time
         const int ch = (8 * ks + 4 * h + q) ^ sw;
         const f32x4 cs = *(LDS_AS const f32x4*)(row + ch * 16);
-        const float la = valid ? bf_lo(lo[q]) * sl2e : 0.0f, lb = valid ? bf_hi(lo[q]) * sl2e : 0.0f;
-        const float ha = valid ? bf_lo(hi[q]) * sl2e : 0.0f, hb = valid ? bf_hi(hi[q]) * sl2e : 0.0f;
+        const float la = bf_lo(lo[q]), lb = bf_hi(lo[q]);
+        const float ha = bf_lo(hi[q]), hb = bf_hi(hi[q]);
         flo[2 * q] = (__bf16)(la * cs[0] - ha * cs[1]);
         fhi[2 * q] = (__bf16)(ha * cs[0] + la * cs[1]);
         flo[2 * q + 1] = (__bf16)(lb * cs[2] - hb * cs[3]);
@@ -181,11 +184,11 @@ __device__ __forceinline__ void rot_frag_half(const u32x4& lo, const u32x4& hi, 
 
 template <int D>
 __device__ __forceinline__ void rotate_q_shared_half(const u32x4 (&raw)[D / 16], LDS_AS const char* tab, int slot, int h,
-                                                     bool valid, float sl2e, bf16x8 (&qf)[D / 16])
+                                                     bf16x8 (&qf)[D / 16])
 {
     LDS_AS const char* row = tab + slot * (4 * D);
 #pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) rot_frag_half<D>(raw[ks], raw[ks + D / 32], row, ks, h, 2 * slot, valid, sl2e, qf[ks], qf[ks + D / 32]);
+    for (int ks = 0; ks < D / 32; ++ks) rot_frag_half<D>(raw[ks], raw[ks + D / 32], row, ks, h, 2 * slot, qf[ks], qf[ks + D / 32]);
 }
 
 // Rotated, scaled queries of a wave from their raw fragments.  slot: which of the wave's tokens this lane's row
@@ -194,15 +197,15 @@ __device__ __forceinline__ void rotate_q_shared_half(const u32x4 (&raw)[D / 16],
 // GQA group is >= 4, up to four for smaller groups.
 template <int D, bool HALF, class PosFn>
 __device__ __forceinline__ void rotate_queries(const u32x4 (&raw)[D / 16], LDS_AS char* tab, double th, int lane, int h, int slot,
-                                               int n_slots, bool valid, float sl2e, PosFn pos_of_slot, bf16x8 (&qf)[D / 16])
+                                               int n_slots, float sl2e, PosFn pos_of_slot, bf16x8 (&qf)[D / 16])
 {
     n_slots = __builtin_amdgcn_readfirstlane(n_slots);
     for (int p0 = 0; p0 < n_slots; p0 += ROT_SLOTS) {
-        build_rot_table<D>(tab, th, lane, pos_of_slot(p0 + (lane & (ROT_SLOTS - 1))));
+        build_rot_table<D>(tab, th, lane, pos_of_slot(p0 + (lane & (ROT_SLOTS - 1))), sl2e);
         const bool mine = (slot >= p0) && (slot < p0 + ROT_SLOTS);
         bf16x8 f[D / 16];
-        if (HALF) rotate_q_shared_half<D>(raw, tab, mine ? slot - p0 : 0, h, valid, sl2e, f);
-        else rotate_q_shared<D>(raw, tab, mine ? slot - p0 : 0, h, valid, sl2e, f);
+        if (HALF) rotate_q_shared_half<D>(raw, tab, mine ? slot - p0 : 0, h, f);
+        else rotate_q_shared<D>(raw, tab, mine ? slot - p0 : 0, h, f);
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks)
             if (mine || p0 == 0) qf[ks] = f[ks]; // the first pass initialises every lane's fragments
@@ -453,7 +456,7 @@ __device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __b
     issue_prologue<D, NW, NS>(k, v, w, smem, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
     LDS_AS char* tab = smem + (NS - 1) * Geo<D>::STAGE_BYTES + wave * (ROT_SLOTS * 4 * D);
-    rotate_queries<D, HALF>(raw, tab, th, lane, h, slot, n_slots, rc.valid, sl2e,
+    rotate_queries<D, HALF>(raw, tab, th, lane, h, slot, n_slots, sl2e,
                             [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
 }
 
@@ -678,7 +681,7 @@ __global__ __launch_bounds__(64 * GATHER_NW, 2) void gather_attn_kernel(const Tr
             const __bf16* qrow = (const __bf16*)a.q + (int64_t)(rc.valid ? rc.orow : 0) * D + 8 * h;
             const int ns = __builtin_amdgcn_readfirstlane(n_slots);
             for (int p0 = 0; p0 < ns; p0 += ROT_SLOTS) { // one pass when the GQA group is >= 4
-                build_rot_table<D>(tab, th, lane, a.q_pos[min(wave_tok0 + p0 + (lane & (ROT_SLOTS - 1)), a.n_q - 1)] - cur_delta);
+                build_rot_table<D>(tab, th, lane, a.q_pos[min(wave_tok0 + p0 + (lane & (ROT_SLOTS - 1)), a.n_q - 1)] - cur_delta, a.scale_log2e);
                 const bool mine = (slot >= p0) && (slot < p0 + ROT_SLOTS);
                 LDS_AS const char* row = tab + (mine ? slot - p0 : 0) * (4 * D);
                 const int sw = 2 * (mine ? slot - p0 : 0);
@@ -696,7 +699,7 @@ __global__ __launch_bounds__(64 * GATHER_NW, 2) void gather_attn_kernel(const Tr
                         for (int i = 0; i < D / 64; ++i) {
                             const int ks = part * (D / 64) + i;
                             bf16x8 flo, fhi;
-                            rot_frag_half<D>(qlo[i], qhi[i], row, ks, h, sw, rc.valid, a.scale_log2e, flo, fhi);
+                            rot_frag_half<D>(qlo[i], qhi[i], row, ks, h, sw, flo, fhi);
                             if (mine || p0 == 0) { qf[ks] = flo; qf[ks + D / 32] = fhi; }
                         }
                     }
@@ -713,10 +716,10 @@ __global__ __launch_bounds__(64 * GATHER_NW, 2) void gather_attn_kernel(const Tr
                             const f32x4 cs0 = *(LDS_AS const f32x4*)(row + ch * 16);
                             const f32x4 cs1 = *(LDS_AS const f32x4*)(row + ch * 16 + 16);
                             bf16x8 f;
-                            rot_pair(raw[i][0], cs0[0], cs0[1], a.scale_log2e, rc.valid, f, 0);
-                            rot_pair(raw[i][1], cs0[2], cs0[3], a.scale_log2e, rc.valid, f, 1);
-                            rot_pair(raw[i][2], cs1[0], cs1[1], a.scale_log2e, rc.valid, f, 2);
-                            rot_pair(raw[i][3], cs1[2], cs1[3], a.scale_log2e, rc.valid, f, 3);
+                            rot_pair(raw[i][0], cs0[0], cs0[1], f, 0);
+                            rot_pair(raw[i][1], cs0[2], cs0[3], f, 1);
+                            rot_pair(raw[i][2], cs1[0], cs1[1], f, 2);
+                            rot_pair(raw[i][3], cs1[2], cs1[3], f, 3);
                             if (mine || p0 == 0) qf[ks] = f;
                         }
                     }
@@ -828,7 +831,7 @@ __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPr
     bf16x8 qf[D / 16];
     {
         LDS_AS char* tab = smem + STAGE + wave * (ROT_SLOTS * 4 * D); // stage 1 is free until the first barrier
-        rotate_queries<D, HALF>(raw, tab, th, lane, h, slot, n_slots, rc.valid, a.scale_log2e,
+        rotate_queries<D, HALF>(raw, tab, th, lane, h, slot, n_slots, a.scale_log2e,
                                 [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
     }
 
