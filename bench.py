@@ -30,12 +30,12 @@ N_VARIANTS = 16
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters read
 # on a copy kernel of known size (the summaries are under profiles/).  None where not measured.
 MEASURED_TRAFFIC = {
-    ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 23825433,       # prefix_attn 16.5 MB (6.2 MB of split partials written) + combine 7.3 MB
-    ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16954640,
-    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268660236,
-    ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174887734,  # prefix_attn 154.9 MB + combine 20.0 MB
-    ("tr_chunk_prefill_attn", "offline-64x512"): 808062056,    # table 0.6 MB + key rotation 135.2 MB + attention 672.3 MB
-    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537995462,
+    ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 23833624,       # prefix_attn 16.5 MB (6.2 MB of split partials written) + combine 7.3 MB
+    ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16961808,
+    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268702313,
+    ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174881462,  # prefix_attn 154.9 MB + combine 20.0 MB
+    ("tr_chunk_prefill_attn", "offline-64x512"): 808676634,    # table 0.6 MB + key rotation 135.7 MB + attention 672.4 MB
+    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537986694,
 }
 
 
