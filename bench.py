@@ -335,10 +335,19 @@ def bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof):
     for ck, cv in caches:
         B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
         B.tr_kv_append(gs, k_q, v_q, q_pos, ck, cv, n_doc)
+    def asm_raw():   # the same bytes moved from a store that is read as un-rotated keys, each turned once at its position id
+        c["i"] += 1
+        ck, cv = caches[c["i"] % 2]
+        B.tr_kv_assemble_raw(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
+
     t_asm = _time_calls(torch, asm, 30)
+    t_raw = _time_calls(torch, asm_raw, 30)
+    for ck, cv in caches:   # the attention below reads the cache formed from the pre-rotated store
+        B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
     t_att = _time_calls(torch, att, 30)
     eb = sh.elem_bytes
     return [hbm_roof("tr_kv_assemble", cfg.name, acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb), t_asm),
+            hbm_roof("tr_kv_assemble_raw", cfg.name, acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb), t_raw),
             mfma_roof("tr_prefill_attn", cfg.name, acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_prefix(req.n_q, kv_len)),
                       t_att, acct.prefill_attn_bytes(req.n_q, kv_len, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb))]
 

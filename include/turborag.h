@@ -102,6 +102,15 @@ int tr_kv_assemble(const tr_store* store, const int32_t* chunk_ids /*host*/, con
                    int32_t n_chunks, int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows,
                    void* stream);
 
+/* The same formation from a store whose k rows are UN-rotated keys (Sec. 3.2: keeping K of Eq. 1 and applying
+ * the position encoding after concatenation; the store handle is created the same way and simply holds raw
+ * keys).  Rows [offsets[i], offsets[i+1]) receive chunk chunk_ids[i]: out_v <- V (copy); out_k <- R(p) K with the
+ * position id p = t (composite) or offsets[i] + t (reordered) of row t of the chunk, in fp64, rounded once - one
+ * rounding where the pre-rotated store has two.  Arguments, plan check and errors as for tr_kv_assemble. */
+int tr_kv_assemble_raw(const tr_store* store, const int32_t* chunk_ids /*host*/, const int64_t* offsets /*host*/,
+                       int32_t n_chunks, int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows,
+                       void* stream);
+
 /* Batched form: request r retrieves chunk_ids[cu_chunks[r] .. cu_chunks[r+1]) and owns cache rows
  * [cache_row_start[r], cache_row_start[r+1]) of out_k/out_v; its documents fill the first n_doc_r rows of
  * that range (the plan is computed here), with pos_modes[r] per request.  All index arrays are host arrays.

@@ -21,7 +21,7 @@ TR_ROPE_INTERLEAVED, TR_ROPE_HALF = 0, 1
 
 EXPORTS = [
     "tr_last_error", "tr_store_create", "tr_store_destroy", "tr_plan",
-    "tr_kv_assemble", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched", "tr_kv_assemble_append",
+    "tr_kv_assemble", "tr_kv_assemble_raw", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched", "tr_kv_assemble_append",
     "tr_prefill_attn_workspace_size", "tr_prefill_attn",
     "tr_prefill_attn_batched_workspace_size", "tr_prefill_attn_batched",
     "tr_prefill_attn_gather_workspace_size", "tr_prefill_attn_gather",
@@ -153,6 +153,14 @@ def tr_kv_assemble(store, chunk_ids, offsets, pos_mode, out_k, out_v, stream=Non
     off, off_p = _host(offsets, np.int64)
     _check(lib().tr_kv_assemble(store.handle, ids_p, off_p, C.c_int32(ids.size), C.c_int32(pos_mode),
                                 _dev(out_k), _dev(out_v), C.c_int64(out_k.shape[0]), _stream(stream)))
+
+
+def tr_kv_assemble_raw(store, chunk_ids, offsets, pos_mode, out_k, out_v, stream=None):
+    """`store` holds un-rotated keys; every key is turned once, at its position id."""
+    ids, ids_p = _host(chunk_ids, np.int32)
+    off, off_p = _host(offsets, np.int64)
+    _check(lib().tr_kv_assemble_raw(store.handle, ids_p, off_p, C.c_int32(ids.size), C.c_int32(pos_mode),
+                                    _dev(out_k), _dev(out_v), C.c_int64(out_k.shape[0]), _stream(stream)))
 
 
 def tr_kv_assemble_batched(store, chunk_ids, cu_chunks, pos_modes, cache_row_start, out_k, out_v, stream=None):

@@ -197,31 +197,42 @@ int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* o
 
 } // namespace
 
-extern "C" int tr_kv_assemble(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
-                              int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
+namespace {
+// Checks one request's plan against the store and lists its chunk runs.
+int request_runs(const char* who, const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
+                 int32_t pos_mode, const void* out_k, const void* out_v, int64_t out_capacity_rows, std::vector<CopyRun>* runs)
 {
-    return tr_guard_int([&]() -> int {
-    tr_clear_error();
-    if (!store || n_chunks < 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_assemble: store NULL or n_chunks < 0");
+    if (!store || n_chunks < 0) return tr_fail(TR_ERR_INVALID_ARG, "%s: store NULL or n_chunks < 0", who);
     if (pos_mode != TR_POS_COMPOSITE && pos_mode != TR_POS_REORDERED) return tr_fail(TR_ERR_INVALID_ARG, "pos_mode %d", pos_mode);
     if (n_chunks == 0) return TR_OK;
     if (!chunk_ids || !offsets) return tr_fail(TR_ERR_INVALID_ARG, "chunk_ids or offsets is NULL");
     if (out_capacity_rows < 0 || out_capacity_rows > ROW_LIMIT) return tr_fail(TR_ERR_INVALID_ARG, "out_capacity_rows out of range");
     const int n_store = (int)store->row_start.size() - 1;
-    std::vector<CopyRun> runs;
-    runs.reserve(n_chunks);
+    runs->reserve(n_chunks);
     int64_t off = 0;
     for (int i = 0; i < n_chunks; ++i) {
         const int32_t c = chunk_ids[i];
         if (c < 0 || c >= n_store) return tr_fail(TR_ERR_BAD_CHUNK_ID, "chunk_ids[%d] = %d outside [0, %d)", i, c, n_store);
         if (offsets[i] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, the prefix sum of the chunk lengths is %lld", i, (long long)offsets[i], (long long)off);
         const int64_t len = store->row_start[c + 1] - store->row_start[c];
-        runs.push_back({store->row_start[c], off, len, pos_mode == TR_POS_REORDERED ? off : 0});
+        runs->push_back({store->row_start[c], off, len, pos_mode == TR_POS_REORDERED ? off : 0});
         off += len;
     }
     if (offsets[n_chunks] != off) return tr_fail(TR_ERR_BAD_PLAN, "offsets[%d] = %lld, expected n_doc = %lld", n_chunks, (long long)offsets[n_chunks], (long long)off);
     if (off > out_capacity_rows) return tr_fail(TR_ERR_BAD_PLAN, "plan needs %lld rows, the cache holds %lld", (long long)off, (long long)out_capacity_rows);
     if (off > 0 && (!out_k || !out_v)) return tr_fail(TR_ERR_INVALID_ARG, "out_k or out_v is NULL");
+    return TR_OK;
+}
+} // namespace
+
+extern "C" int tr_kv_assemble(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
+                              int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
+{
+    return tr_guard_int([&]() -> int {
+    tr_clear_error();
+    std::vector<CopyRun> runs;
+    const int rc = request_runs("tr_kv_assemble", store, chunk_ids, offsets, n_chunks, pos_mode, out_k, out_v, out_capacity_rows, &runs);
+    if (rc) return rc;
     return launch_runs(store, runs, out_k, out_v, (hipStream_t)stream);
     });
 }
@@ -386,6 +397,7 @@ extern "C" int tr_kv_append_batched(const tr_shape* shape, const void* k_new, co
         if (n_q < 0 || len < 0) return tr_fail(TR_ERR_INVALID_ARG, "cu_q or cache_row_start decreases at request %d", r);
         if (n_q > len) return tr_fail(TR_ERR_BAD_PLAN, "request %d: %d query tokens, cache range of %lld rows", r, n_q, (long long)len);
         TrAppendDesc e;
+        e.pos0 = 0;
         e.q_row0 = cu_q[r];
         e.n_q = n_q;
         e.dst_row0 = (int32_t)(cache_row_start[r + 1] - n_q);
@@ -393,6 +405,31 @@ extern "C" int tr_kv_append_batched(const tr_shape* shape, const void* k_new, co
     }
     if (cu_q[n_req] > 0 && (!k_new || !v_new || !q_pos || !cache_k || !cache_v)) return tr_fail(TR_ERR_INVALID_ARG, "tr_kv_append_batched: NULL pointer");
     return launch_append(shape, k_new, v_new, q_pos, d, cache_k, cache_v, (hipStream_t)stream);
+    });
+}
+
+// ---- KV-cache formation from a store of UN-rotated keys (Sec. 3.2: keep K of Eq. 1, rotate after concatenation) ------
+extern "C" int tr_kv_assemble_raw(const tr_store* store, const int32_t* chunk_ids, const int64_t* offsets, int32_t n_chunks,
+                                  int32_t pos_mode, void* out_k, void* out_v, int64_t out_capacity_rows, void* stream)
+{
+    return tr_guard_int([&]() -> int {
+    tr_clear_error();
+    std::vector<CopyRun> runs;
+    const int rc = request_runs("tr_kv_assemble_raw", store, chunk_ids, offsets, n_chunks, pos_mode, out_k, out_v, out_capacity_rows, &runs);
+    if (rc) return rc;
+    // every row is a token whose key is turned once, at its position id (the run's first id plus the row's index):
+    // the arithmetic of the query append, one thread per (row, channel pair)
+    std::vector<TrAppendDesc> d;
+    d.reserve(runs.size());
+    for (const CopyRun& r : runs) {
+        TrAppendDesc e;
+        e.q_row0 = (int32_t)r.src_row;
+        e.n_q = (int32_t)r.n_rows;
+        e.dst_row0 = (int32_t)r.dst_row;
+        e.pos0 = (int32_t)r.delta;
+        d.push_back(e);
+    }
+    return launch_append(&store->shape, store->k, store->v, nullptr, d, out_k, out_v, (hipStream_t)stream);
     });
 }
 

@@ -134,7 +134,7 @@ constexpr int APPEND_MAX_HEADS = 16; // KV heads held in registers at once; more
 
 // The same for the half-split layout: the pair is (channel m, channel m + d/2) of every head.
 template <int DTYPE>
-__device__ __forceinline__ void append_pair_half(const void* k_new, const void* v_new, const int32_t* q_pos, void* cache_k,
+__device__ __forceinline__ void append_pair_half(const void* k_new, const void* v_new, int pos, void* cache_k,
                                                  void* cache_v, int n_kv_heads, int half, double theta_m, int64_t src_row,
                                                  int64_t dst_row, int m)
 {
@@ -144,7 +144,7 @@ __device__ __forceinline__ void append_pair_half(const void* k_new, const void* 
     const Elem* vs = (const Elem*)v_new + src_row * n_kv_heads * d + m;
     Elem* kd = (Elem*)cache_k + dst_row * n_kv_heads * d + m;
     Elem* vd = (Elem*)cache_v + dst_row * n_kv_heads * d + m;
-    const double angle = (double)q_pos[src_row] * theta_m;
+    const double angle = (double)pos * theta_m;
     double sn = 0.0, cn = 1.0;
     for (int h0 = 0; h0 < n_kv_heads; h0 += APPEND_MAX_HEADS) {
         Elem ka[APPEND_MAX_HEADS], kb[APPEND_MAX_HEADS], va[APPEND_MAX_HEADS], vb[APPEND_MAX_HEADS];
@@ -184,12 +184,12 @@ __device__ __forceinline__ void append_pair_half(const void* k_new, const void* 
 // The angle is shared by all KV heads of the token (the fp64 sincos is by far the longest thing a thread does, so
 // it is done once per thread), and the loads go out before it.
 template <int DTYPE, bool HALF>
-__device__ __forceinline__ void append_pair(const void* k_new, const void* v_new, const int32_t* q_pos, void* cache_k,
+__device__ __forceinline__ void append_pair(const void* k_new, const void* v_new, int pos, void* cache_k,
                                             void* cache_v, int n_kv_heads, int half, double theta_m, int64_t src_row,
                                             int64_t dst_row, int m)
 {
     if constexpr (HALF) {
-        append_pair_half<DTYPE>(k_new, v_new, q_pos, cache_k, cache_v, n_kv_heads, half, theta_m, src_row, dst_row, m);
+        append_pair_half<DTYPE>(k_new, v_new, pos, cache_k, cache_v, n_kv_heads, half, theta_m, src_row, dst_row, m);
         return;
     }
     typedef typename std::conditional<DTYPE == TR_BF16, uint32_t, float2>::type Pair; // one (even, odd) channel pair
@@ -197,7 +197,7 @@ __device__ __forceinline__ void append_pair(const void* k_new, const void* v_new
     const Pair* vs = (const Pair*)v_new + src_row * n_kv_heads * half + m;
     Pair* kd = (Pair*)cache_k + dst_row * n_kv_heads * half + m;
     Pair* vd = (Pair*)cache_v + dst_row * n_kv_heads * half + m;
-    const double angle = (double)q_pos[src_row] * theta_m;
+    const double angle = (double)pos * theta_m;
     double sn = 0.0, cn = 1.0;
     for (int h0 = 0; h0 < n_kv_heads; h0 += APPEND_MAX_HEADS) {
         Pair kx[APPEND_MAX_HEADS], vx[APPEND_MAX_HEADS];
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)
         const int gid = (b - a.app.first_block) * 256 + (int)threadIdx.x;
         const int tok = gid / a.half_dim, m = gid % a.half_dim;
         if (tok < a.app.n_q)
-            append_pair<DTYPE, HALF>(a.app.k_new, a.app.v_new, a.app.q_pos, a.k_dst, a.v_dst, a.app.n_kv_heads, a.half_dim,
+            append_pair<DTYPE, HALF>(a.app.k_new, a.app.v_new, a.app.q_pos[tok], a.k_dst, a.v_dst, a.app.n_kv_heads, a.half_dim,
                                      a.theta[m], tok, (int64_t)a.app.dst_row0 + tok, m);
         return;
     }
@@ -346,7 +346,9 @@ __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
     int r = 0, base = 0;
     while (r + 1 < a.n_desc && tok >= base + a.desc[r].n_q) { base += a.desc[r].n_q; ++r; }
     const int i = tok - base;
-    append_pair<DTYPE, HALF>(a.k_new, a.v_new, a.q_pos, a.cache_k, a.cache_v, a.n_kv_heads, half, a.theta[m],
+    // position id: the caller's, or (raw-store assembly) the run's first position plus the row's index in the run
+    const int pos = a.q_pos ? a.q_pos[a.desc[r].q_row0 + i] : a.desc[r].pos0 + i;
+    append_pair<DTYPE, HALF>(a.k_new, a.v_new, pos, a.cache_k, a.cache_v, a.n_kv_heads, half, a.theta[m],
                              (int64_t)a.desc[r].q_row0 + i, (int64_t)a.desc[r].dst_row0 + i, m);
 }
 

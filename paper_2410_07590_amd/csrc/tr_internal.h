@@ -73,6 +73,7 @@ struct TrAppendDesc {
     int32_t q_row0;
     int32_t n_q;
     int32_t dst_row0;
+    int32_t pos0; // position id of the first token when the launch carries no q_pos array (raw-store assembly)
 };
 #define TR_MAX_APPEND_DESC 128
 struct TrAppendArgs {

@@ -148,14 +148,15 @@ def test_plan_errors(L):
     L.tr_store_destroy(h)
 
 
-def test_assemble_validation_happens_before_any_enqueue(L):
+@pytest.mark.parametrize("entry", ["tr_kv_assemble", "tr_kv_assemble_raw"])
+def test_assemble_validation_happens_before_any_enqueue(L, entry):
     rc, h = _store(L, _shape(), [0, 4, 9, 9, 20])
     assert rc == B.TR_OK
     ids, ids_p = _i32([1, 3, 0])
     good, good_p = _i64([0, 5, 16, 20])
 
     def call(ids_p=ids_p, off_p=good_p, n=3, mode=B.TR_POS_REORDERED, k=FAKE, v=FAKE2, cap=64, store=h):
-        return L.tr_kv_assemble(store, ids_p, off_p, C.c_int32(n), C.c_int32(mode), k, v, C.c_int64(cap), None)
+        return getattr(L, entry)(store, ids_p, off_p, C.c_int32(n), C.c_int32(mode), k, v, C.c_int64(cap), None)
 
     assert call(cap=19) == B.TR_ERR_BAD_PLAN                       # does not fit
     bad, bad_p = _i64([0, 5, 15, 20])

@@ -439,6 +439,36 @@ def test_offline_store_feeds_online_path(B):
     assert err <= H.BF16_TOL, err
 
 
+# ---- a store of un-rotated keys: every key turned once, at its position id (Sec. 3.2) ----------------------------
+@pytest.mark.parametrize("mode", [synth.POS_COMPOSITE, synth.POS_REORDERED])
+@pytest.mark.parametrize("case", [(synth.QWEN2_7B, (37, 64, 129, 0, 200, 1), (2, 0, 3, 4, 1, 0, 5)),
+                                  (synth.Shape(32, 8, 128, "bf16", 5e5, 1), (300, 17, 255), (1, 2, 0)),
+                                  (synth.Shape(16, 2, 64, "bf16", 1e4), (130, 61, 77), (2, 1, 0, 2)),
+                                  (synth.Shape(4, 4, 64, "f32", 1e4), (64, 40), (1, 0, 1)),
+                                  (synth.Shape(40, 20, 128, "bf16", 1e4, 1), (50, 9), (0, 1))])
+def test_assemble_from_raw_keys(B, case, mode):
+    sh, lens, ids = case
+    rng = np.random.Generator(np.random.PCG64([123, len(lens)]))
+    row_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rows = int(row_start[-1])
+    raw = synth.Store(synth.normal_tensor(rng, (rows, sh.n_kv_heads, sh.head_dim), sh.torch_dtype),
+                      synth.normal_tensor(rng, (rows, sh.n_kv_heads, sh.head_dim), sh.torch_dtype), row_start)
+    sd = _store_dev(B, sh, raw)
+    ids = np.asarray(ids, np.int32)
+    offsets, pos = B.tr_plan(sd, ids, mode)
+    n_doc = int(offsets[-1])
+    ck = torch.full((n_doc + 2, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=sh.torch_dtype, device="cuda")
+    cv = torch.full_like(ck, float("nan"))
+    B.tr_kv_assemble_raw(sd, ids, offsets, mode, ck, cv)
+    torch.cuda.synchronize()
+    src = np.concatenate([np.arange(row_start[c], row_start[c + 1]) for c in ids]).astype(np.int64)
+    want_k = oracle.round_to(oracle.rope(H.bits(raw.k)[src], pos, sh.rope_base, sh.rope_layout), oracle.F32 if sh.dtype == "f32" else oracle.BF16)
+    H.assert_same_bits(H.bits(cv.cpu())[:n_doc], H.bits(raw.v)[src], "V gathered from the raw store")
+    n_bad = H.assert_same_bits(H.bits(ck.cpu())[:n_doc], want_k, "raw keys rotated at their position ids", 1e-5)
+    assert torch.isnan(ck[n_doc:].float()).all() and torch.isnan(cv[n_doc:].float()).all()      # nothing written past the end
+    print("raw-store assemble %s mode %d: %d rows, one-ulp mismatches %d" % (sh, mode, n_doc, n_bad))
+
+
 # ---- one pass over [chunks, query/answer] with the masks and position ids of inference (Sec. 3.3) ---------------
 def _run_sequence(B, sh, q, k, v, seg, pos, host_copy=True):
     """host_copy: hand the library the host array of the starts, so that it may cut long key ranges into pieces."""
