@@ -239,6 +239,7 @@ def main():
         roof_extra += bench_decode(torch, B, synth, hbm_roof)
         if args.host_store:
             roof_extra += bench_host_store(torch, B, synth, acct)
+        result["layer_context"] = bench_layer_context(torch, B, synth)
         result["hbm_copy_ceiling_gbs"] = measured_copy_rate(torch)
         result["cpu_baseline"] = cpu_baseline(synth, cfg)
     result["roofline_extra"] = roof_extra
@@ -438,6 +439,57 @@ def bench_sequence(torch, B, synth, acct, mfma_roof):
                   acct.chunk_prefill_bytes(T, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.elem_bytes))
     r["note"] = "whole call: key rotation at the position ids + one attention pass over documents and query"
     return [r]
+
+
+def bench_layer_context(torch, B, synth):
+    """Context figure, not a roofline row: the attention block of one layer around the step - query/key/value
+    projections of the query tokens' hidden states, the step (assemble and append + prefill attention), the output
+    projection - at the Qwen2-7B shape with random weights.  The four projections are plain library GEMMs
+    (torch.matmul) outside the C boundary; biases, norms and the MLP are not part of it.  Two workloads:
+    configuration 2, and the shape of the paper's Table 4 (16 chunks x 512 tokens, 128 query tokens)."""
+    sh = synth.QWEN2_7B
+    hidden = sh.n_q_heads * sh.head_dim
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20241013)
+    rnd = lambda *shape, scale=1.0: (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * scale).to(torch.bfloat16)
+    wq, wo = rnd(hidden, hidden, scale=hidden ** -0.5), rnd(hidden, hidden, scale=hidden ** -0.5)
+    wk, wv = (rnd(hidden, sh.n_kv_heads * sh.head_dim, scale=hidden ** -0.5) for _ in range(2))
+    rows = []
+    for name, n_chunks, n_q in (("qwen2-7b-8x512-q64", 8, 64), ("table4-shape-16x512-q128", 16, 128)):
+        n_store = 64
+        ks, vs = rnd(n_store * 512, sh.n_kv_heads, sh.head_dim), rnd(n_store * 512, sh.n_kv_heads, sh.head_dim)
+        sd = B.Store(gs, ks, vs, np.arange(n_store + 1, dtype=np.int64) * 512)
+        ids = np.random.default_rng(7).permutation(n_store)[:n_chunks].astype(np.int32)
+        n_doc = n_chunks * 512
+        kv_len = n_doc + n_q
+        x = rnd(n_q, hidden)
+        q, o = torch.empty((n_q, sh.n_q_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda"), None
+        kq, vq = (torch.empty((n_q, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+        ck = torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
+        cv, att = torch.empty_like(ck), torch.empty_like(q)
+        o = torch.empty((n_q, hidden), dtype=torch.bfloat16, device="cuda")
+        q_pos = torch.arange(n_doc, kv_len, dtype=torch.int32, device="cuda")
+        ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, n_q, kv_len))
+
+        def step():
+            offsets, _ = B.tr_plan(sd, ids, synth.POS_REORDERED, want_pos_ids=False)
+            B.tr_kv_assemble_append(sd, ids, offsets, synth.POS_REORDERED, kq, vq, q_pos, ck, cv)
+            B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, att, ws)
+
+        def layer():
+            torch.matmul(x, wq, out=q.view(n_q, hidden))
+            torch.matmul(x, wk, out=kq.view(n_q, -1))
+            torch.matmul(x, wv, out=vq.view(n_q, -1))
+            step()
+            torch.matmul(att.view(n_q, hidden), wo, out=o)
+
+        t_layer = _time_calls(torch, layer, 20)
+        t_step = _time_calls(torch, step, 20)
+        rows.append({"workload": name, "attention_block_us": round(t_layer[0], 2), "step_us": round(t_step[0], 2),
+                     "projections_us": round(t_layer[0] - t_step[0], 2)})
+    return {"what": "attention block of one layer: q/k/v projections (library GEMMs, random weights) + step + output projection",
+            "rows": rows}
 
 
 DECODE_BATCH, DECODE_KV = 64, 4096

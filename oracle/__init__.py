@@ -267,3 +267,10 @@ def masked_prefill(q, k, v, lo, pos, base, layout=ROPE_INTERLEAVED, rows=None, s
     res["out"] = attn_rows(q_rot, k_rot, widen(v), lo, rows)
     res["k_rot"] = k_rot
     return res
+
+
+def linear(x, w):
+    """Projection of Eq. 1 (X W for the query, key and value weights; the output projection is the same product):
+    y[m, n] = sum_k x[m, k] w[n, k], with w stored [out_features, in_features].  x, w: storage-typed arrays; returns
+    float64 [M, N].  The contraction is numpy's matmul on the widened operands."""
+    return np.matmul(widen(x), widen(w).T)

@@ -508,7 +508,7 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
     const int wg_rows = pick_wg_rows(sh, max_rows);
     const int tpt = wg_rows / g;
     const int target = env_int("TR_TARGET_ITEMS", TARGET_ITEMS);
-    const int min_split_keys = env_int("TR_MIN_SPLIT_KEYS", MIN_SPLIT_KEYS);
+    const int min_split_keys = std::max(KEY_TILE, env_int("TR_MIN_SPLIT_KEYS", MIN_SPLIT_KEYS));
     int64_t base_items = 0;
     for (size_t r = r0; r < r1; ++r) base_items += (int64_t)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads;
     int want_split = 1;
@@ -928,7 +928,8 @@ int64_t plan_blockdiag(const tr_shape* sh, const int32_t* start_host, int64_t T,
             span[(size_t)tile] = (int32_t)(t1 - lo);
             walked += (double)((t1 - lo + KEY_TILE - 1) / KEY_TILE);
         }
-        const double fair = walked * sh->n_kv_heads / env_int("TR_BD_SLOTS", BD_SLOTS); // key tiles per resident workgroup
+        const int slots = std::max(1, env_int("TR_BD_SLOTS", BD_SLOTS));
+        const double fair = walked * sh->n_kv_heads / slots; // key tiles per resident workgroup
         int piece = (int)(fair / 3.0);
         if (piece < BD_MIN_PIECE_TILES) piece = BD_MIN_PIECE_TILES;
         piece = env_int("TR_BD_PIECE_TILES", piece);
