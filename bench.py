@@ -442,19 +442,18 @@ def bench_sequence(torch, B, synth, acct, mfma_roof):
 
 
 def bench_layer_context(torch, B, synth):
-    """Context figure, not a roofline row: the attention block of one layer around the step - query/key/value
-    projections of the query tokens' hidden states, the step (assemble and append + prefill attention), the output
-    projection - at the Qwen2-7B shape with random weights.  The four projections are plain library GEMMs
-    (torch.matmul) outside the C boundary; biases, norms and the MLP are not part of it.  Two workloads:
-    configuration 2, and the shape of the paper's Table 4 (16 chunks x 512 tokens, 128 query tokens)."""
+    """The attention block of one layer around the step: query/key/value projections of the query tokens' hidden
+    states (Eq. 1), the step (assemble and append + prefill attention), the output projection, at the Qwen2-7B shape
+    with random weights; biases, norms and the MLP are not part of it.  Two workloads: configuration 2, and the shape
+    of the paper's Table 4 (16 chunks x 512 tokens, 128 query tokens)."""
     sh = synth.QWEN2_7B
     hidden = sh.n_q_heads * sh.head_dim
     gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20241013)
     rnd = lambda *shape, scale=1.0: (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * scale).to(torch.bfloat16)
-    wq, wo = rnd(hidden, hidden, scale=hidden ** -0.5), rnd(hidden, hidden, scale=hidden ** -0.5)
-    wk, wv = (rnd(hidden, sh.n_kv_heads * sh.head_dim, scale=hidden ** -0.5) for _ in range(2))
+    wq, wo = rnd(hidden, hidden, scale=hidden ** -0.5), rnd(hidden, hidden, scale=hidden ** -0.5)   # [out_features, in_features]
+    wk, wv = (rnd(sh.n_kv_heads * sh.head_dim, hidden, scale=hidden ** -0.5) for _ in range(2))
     rows = []
     for name, n_chunks, n_q in (("qwen2-7b-8x512-q64", 8, 64), ("table4-shape-16x512-q128", 16, 128)):
         n_store = 64
@@ -477,18 +476,36 @@ def bench_layer_context(torch, B, synth):
             B.tr_kv_assemble_append(sd, ids, offsets, synth.POS_REORDERED, kq, vq, q_pos, ck, cv)
             B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, att, ws)
 
-        def layer():
-            torch.matmul(x, wq, out=q.view(n_q, hidden))
-            torch.matmul(x, wk, out=kq.view(n_q, -1))
-            torch.matmul(x, wv, out=vq.view(n_q, -1))
+        def layer_library():
+            torch.matmul(x, wq.t(), out=q.view(n_q, hidden))
+            torch.matmul(x, wk.t(), out=kq.view(n_q, -1))
+            torch.matmul(x, wv.t(), out=vq.view(n_q, -1))
             step()
-            torch.matmul(att.view(n_q, hidden), wo, out=o)
+            torch.matmul(att.view(n_q, hidden), wo.t(), out=o)
+
+        ws_qkv = B.workspace(B.tr_linear_workspace_size(n_q, [wq.shape[0], wk.shape[0], wv.shape[0]], hidden))
+        ws_o = B.workspace(B.tr_linear_workspace_size(n_q, [hidden], hidden))
+
+        def layer():
+            B.tr_linear(x, [wq, wk, wv], [q, kq, vq], ws_qkv)
+            step()
+            B.tr_linear(att.view(n_q, hidden), wo, o, ws_o)
+
+        def projections():
+            B.tr_linear(x, [wq, wk, wv], [q, kq, vq], ws_qkv)
+            B.tr_linear(att.view(n_q, hidden), wo, o, ws_o)
 
         t_layer = _time_calls(torch, layer, 20)
+        t_lib = _time_calls(torch, layer_library, 20)
         t_step = _time_calls(torch, step, 20)
+        t_proj = _time_calls(torch, projections, 20)
+        w_bytes = 2 * (wq.numel() + wk.numel() + wv.numel() + wo.numel())
         rows.append({"workload": name, "attention_block_us": round(t_layer[0], 2), "step_us": round(t_step[0], 2),
-                     "projections_us": round(t_layer[0] - t_step[0], 2)})
-    return {"what": "attention block of one layer: q/k/v projections (library GEMMs, random weights) + step + output projection",
+                     "tr_linear_us": round(t_proj[0], 2), "weight_bytes": w_bytes,
+                     "weight_stream_gbs": round(w_bytes / (t_proj[0] * 1e-6) / 1e9, 1),
+                     "attention_block_with_library_gemms_us": round(t_lib[0], 2)})
+    return {"what": "attention block of one layer: q/k/v projection (tr_linear, one launch for the three weights, random weights) + "
+                    "step + output projection (tr_linear); the same block with torch.matmul for the projections beside it",
             "rows": rows}
 
 

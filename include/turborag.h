@@ -237,6 +237,22 @@ int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, const void* k
                              const int32_t* seg_start_host /*host, may be NULL*/, int64_t total_tokens,
                              void* out, void* k_rot_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- projections around the attention for the query tokens (Eq. 1: Q, K, V = X W; the output projection is the
+ * same product) ---------------------------------------------------------------------------------------------------------
+ * For j < n_out (1 .. 4 weights that share x, e.g. query, key and value in one launch):
+ *   y[j][m, n] = sum_k x[m, k] w[j][n, k],
+ * x device [M, K]; w[j] device [n_features[j], K] (the layout of a linear layer's weight: out_features x in_features);
+ * y[j] device [M, n_features[j]]; all bf16, fp32 accumulation, one rounding of the result.  w, y: HOST arrays of
+ * n_out device pointers, n_features: host array, all consumed before the call returns.
+ * M <= 128 (the weights are streamed from HBM exactly once, which is what bounds a product with so few rows; more
+ * rows: TR_ERR_UNSUPPORTED - that is a library GEMM's work); every n_features[j] a multiple of 32 and K a multiple
+ * of 16 (else TR_ERR_SHAPE); x and w[j] 16-byte aligned.  M == 0 is a no-op.  workspace:
+ * tr_linear_workspace_size() bytes (fp32 partial sums of the slices of k that run in different workgroups; 0 when
+ * there is one slice), 256-byte aligned, else TR_ERR_WORKSPACE. */
+size_t tr_linear_workspace_size(int32_t M, int32_t n_out, const int32_t* n_features /*host*/, int32_t K);
+int tr_linear(const void* x, int32_t M, int32_t K, int32_t n_out, const void* const* w /*host*/, void* const* y /*host*/,
+              const int32_t* n_features /*host*/, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,7 @@ EXPORTS = [
     "tr_decode_attn_workspace_size", "tr_decode_attn",
     "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
     "tr_sequence_plan", "tr_sequence_prefill_attn_workspace_size", "tr_sequence_prefill_attn",
+    "tr_linear_workspace_size", "tr_linear",
 ]
 
 
@@ -60,7 +61,8 @@ def lib():
         L.tr_last_error.restype = C.c_char_p
         for name in ("tr_prefill_attn_workspace_size", "tr_prefill_attn_batched_workspace_size",
                      "tr_prefill_attn_gather_workspace_size", "tr_decode_attn_workspace_size",
-                     "tr_chunk_prefill_attn_workspace_size", "tr_sequence_prefill_attn_workspace_size"):
+                     "tr_chunk_prefill_attn_workspace_size", "tr_sequence_prefill_attn_workspace_size",
+                     "tr_linear_workspace_size"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -284,6 +286,30 @@ def tr_sequence_prefill_attn(shape, q, k, v, seg_start, pos, out, k_rot_out, seg
     _check(lib().tr_sequence_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(seg_start), _dev(pos), hp,
                                           C.c_int64(q.shape[0]), _dev(out), _dev(k_rot_out), _dev(workspace),
                                           C.c_size_t(0 if workspace is None else workspace.numel()), _stream(stream)))
+
+
+def _features(n_features):
+    f = np.atleast_1d(np.asarray(n_features, dtype=np.int32))
+    return f, f.ctypes.data_as(C.c_void_p)
+
+
+def tr_linear_workspace_size(M, n_features, K):
+    f, fp = _features(n_features)
+    return int(lib().tr_linear_workspace_size(C.c_int32(M), C.c_int32(f.size), fp, C.c_int32(K)))
+
+
+def tr_linear(x, w, y, workspace=None, stream=None):
+    """y[j][M, N_j] = x[M, K] @ w[j][N_j, K]^T, bf16, at most 128 rows of x.  w, y: one tensor each, or lists of up to four
+    that share x."""
+    ws_, ys_ = (list(w), list(y)) if isinstance(w, (list, tuple)) else ([w], [y])
+    M, K = x.shape
+    for wj, yj in zip(ws_, ys_):
+        assert wj.shape[1] == K and yj.numel() == M * wj.shape[0]
+    f, fp = _features([wj.shape[0] for wj in ws_])
+    wp = (C.c_void_p * len(ws_))(*[_dev(t) for t in ws_])
+    yp = (C.c_void_p * len(ys_))(*[_dev(t) for t in ys_])
+    _check(lib().tr_linear(_dev(x), C.c_int32(M), C.c_int32(K), C.c_int32(len(ws_)), wp, yp, fp, _dev(workspace),
+                           C.c_size_t(0 if workspace is None else workspace.numel()), _stream(stream)))
 
 
 def workspace(nbytes, device="cuda"):

@@ -1094,6 +1094,68 @@ extern "C" int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, co
     });
 }
 
+// ---- projections around the attention (Eq. 1) for the query tokens ------------------------------------------------------
+namespace {
+constexpr int LINEAR_MAX_ROWS = 128;
+// returns the status and, through n_total, the summed feature count
+int check_linear(int32_t M, int32_t n_out, const int32_t* n_features, int32_t K, int64_t* n_total)
+{
+    if (M < 0 || K <= 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: M %d, K %d", M, K);
+    if (n_out < 1 || n_out > TR_LINEAR_MAX_OUT) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: %d outputs, 1 .. %d supported", n_out, TR_LINEAR_MAX_OUT);
+    if (!n_features) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: n_features is NULL");
+    int64_t N = 0;
+    for (int j = 0; j < n_out; ++j) {
+        if (n_features[j] <= 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: n_features[%d] = %d", j, n_features[j]);
+        if (n_features[j] % 32 != 0) return tr_fail(TR_ERR_SHAPE, "tr_linear: n_features[%d] = %d is not a multiple of 32", j, n_features[j]);
+        N += n_features[j];
+    }
+    if (K % 16 != 0) return tr_fail(TR_ERR_SHAPE, "tr_linear: K (%d) must be a multiple of 16", K);
+    if (N > (1 << 24)) return tr_fail(TR_ERR_UNSUPPORTED, "tr_linear: %lld output features", (long long)N);
+    if (M > LINEAR_MAX_ROWS) return tr_fail(TR_ERR_UNSUPPORTED, "tr_linear streams the weights once for at most %d rows of x (got %d); larger products are a library GEMM's work", LINEAR_MAX_ROWS, M);
+    *n_total = N;
+    return TR_OK;
+}
+size_t linear_ws_bytes(int32_t M, int64_t N, int32_t K)
+{
+    const int n_split = tr_linear_splits((int32_t)N, K);
+    return n_split > 1 ? tr_align256((size_t)n_split * M * N * 4) : 0;
+}
+} // namespace
+
+extern "C" size_t tr_linear_workspace_size(int32_t M, int32_t n_out, const int32_t* n_features, int32_t K)
+{
+    return tr_guard_size([&]() -> size_t {
+    int64_t N = 0;
+    if (check_linear(M, n_out, n_features, K, &N) || M == 0) return 0;
+    return linear_ws_bytes(M, N, K);
+    });
+}
+
+extern "C" int tr_linear(const void* x, int32_t M, int32_t K, int32_t n_out, const void* const* w, void* const* y,
+                         const int32_t* n_features, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return tr_guard_int([&]() -> int {
+    tr_clear_error();
+    int64_t N = 0;
+    const int rc = check_linear(M, n_out, n_features, K, &N);
+    if (rc) return rc;
+    if (M == 0) return TR_OK;
+    if (!x || !w || !y) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: NULL pointer");
+    if (((uintptr_t)x & 15) != 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: x must be 16-byte aligned");
+    for (int j = 0; j < n_out; ++j) {
+        if (!w[j] || !y[j]) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: w[%d] or y[%d] is NULL", j, j);
+        if (((uintptr_t)w[j] & 15) != 0 || ((uintptr_t)y[j] & 7) != 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_linear: w[%d] must be 16-byte aligned, y[%d] 8-byte aligned", j, j);
+    }
+    const size_t need = linear_ws_bytes(M, N, K);
+    if (need > 0) {
+        if (!workspace) return tr_fail(TR_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+        if (((uintptr_t)workspace & 255) != 0) return tr_fail(TR_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+        if (workspace_bytes < need) return tr_fail(TR_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    }
+    return tr_launch_linear(x, n_out, w, y, n_features, need > 0 ? workspace : nullptr, M, K, (hipStream_t)stream);
+    });
+}
+
 // ---- decode step: one query token per request ---------------------------------------------------------------------
 namespace {
 int decode_cu(int32_t n_req, std::vector<int32_t>* cu)

@@ -384,3 +384,43 @@ def test_assemble_append_and_decode_validation(L):
     assert L.tr_decode_attn(C.byref(sh), None, FAKE, FAKE, FAKE, ok_p, C.c_int32(3), FAKE, None, C.c_size_t(0), None) == B.TR_ERR_INVALID_ARG
     assert L.tr_decode_attn(C.byref(sh), FAKE, FAKE, FAKE, FAKE, ok_p, C.c_int32(-1), FAKE, None, C.c_size_t(0), None) == B.TR_ERR_INVALID_ARG
     assert L.tr_decode_attn(C.byref(sh), FAKE, FAKE, FAKE, FAKE, ok_p, C.c_int32(0), FAKE, None, C.c_size_t(0), None) == B.TR_OK
+
+
+def test_linear_validation(L):
+    L.tr_linear_workspace_size.restype = C.c_size_t
+    ptrs = lambda *vals: (C.c_void_p * len(vals))(*vals)
+
+    def call(x=FAKE, M=64, K=3584, feats=(3584,), w=None, y=None, ws=FAKE, ws_bytes=1 << 30, n_out=None):
+        f, f_p = _i32(list(feats))
+        n = len(feats) if n_out is None else n_out
+        w = ptrs(*([0x10000] * len(feats))) if w is None else w
+        y = ptrs(*([0x20000] * len(feats))) if y is None else y
+        return L.tr_linear(x, C.c_int32(M), C.c_int32(K), C.c_int32(n), w, y, f_p, ws, C.c_size_t(ws_bytes), None)
+
+    assert call(M=0) == B.TR_OK                                      # nothing to do, nothing enqueued
+    assert call(x=None) == B.TR_ERR_INVALID_ARG
+    assert call(w=ptrs(0)) == B.TR_ERR_INVALID_ARG
+    assert call(y=ptrs(0)) == B.TR_ERR_INVALID_ARG
+    assert call(M=-1) == B.TR_ERR_INVALID_ARG
+    assert call(feats=(0,)) == B.TR_ERR_INVALID_ARG
+    assert call(n_out=0) == B.TR_ERR_INVALID_ARG
+    assert call(feats=(32,) * 5) == B.TR_ERR_INVALID_ARG             # at most four weights share x
+    assert call(feats=(3600,)) == B.TR_ERR_SHAPE                     # not a multiple of 32
+    assert call(feats=(3584, 500, 512)) == B.TR_ERR_SHAPE
+    assert call(K=3590) == B.TR_ERR_SHAPE                            # not a multiple of 16
+    assert call(M=129) == B.TR_ERR_UNSUPPORTED                       # more rows than the weight-streaming kernel takes
+    assert call(x=C.c_void_p(0x1008)) == B.TR_ERR_INVALID_ARG        # misaligned operand
+    assert call(w=ptrs(0x10008)) == B.TR_ERR_INVALID_ARG
+    one, one_p = _i32([3584])
+    size = L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), one_p, C.c_int32(3584))
+    assert size > 0 and size % 256 == 0 and size % (64 * 3584 * 4) == 0          # whole fp32 slices of y
+    assert call(ws=None) == B.TR_ERR_WORKSPACE
+    assert call(ws_bytes=size - 256) == B.TR_ERR_WORKSPACE
+    assert call(ws=C.c_void_p(0x1010)) == B.TR_ERR_WORKSPACE
+    qkv, qkv_p = _i32([3584, 512, 512])
+    fused = L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(3), qkv_p, C.c_int32(3584))
+    assert fused % (64 * 4608 * 4) == 0 and fused > 0                # slices of all three outputs side by side
+    big, big_p = _i32([32768])
+    assert L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), big_p, C.c_int32(3584)) == 0   # enough row tiles: no slicing
+    bad, bad_p = _i32([3600])
+    assert L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), bad_p, C.c_int32(3584)) == 0   # invalid shape: 0

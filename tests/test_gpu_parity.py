@@ -633,3 +633,33 @@ def test_half_layout_offline_and_one_pass(B, dtype):
     if dtype == "bf16":   # head_dim 64, GQA group 7
         sh64 = synth.Shape(14, 2, 64, "bf16", 1e6, HALF)
         print("half layout, one pass d=64: max abs err %.3e" % _check_sequence(B, sh64, (90, 40), 25, synth.POS_REORDERED, 330))
+
+
+# ---- projections around the attention (Eq. 1), query tokens only ------------------------------------------------------
+LINEAR_CASES = [(64, (3584,), 3584), (128, (3584, 512, 512), 3584), (1, (512,), 3584), (37, (96,), 48), (100, (32,), 16),
+                (128, (18944,), 3584), (33, (64, 32, 32, 64), 2048), (64, (3584,), 18944)]
+
+
+@pytest.mark.parametrize("case", range(len(LINEAR_CASES)))
+def test_linear_against_fp64_matmul(B, case):
+    """y_j = x W_j^T at the Qwen2-7B projection sizes (hidden 3584: query, key and value weights in one launch, the
+    output projection, the key rows alone, the MLP's two sizes) and at ragged small ones (rows not a multiple of 32,
+    one k-step, one row tile, four outputs).  Bar: one bf16 rounding of a value accumulated in fp32,
+    |err| <= 2^-8 |y| + 1e-3."""
+    M, feats, K = LINEAR_CASES[case]
+    rng = np.random.Generator(np.random.PCG64([500, case]))
+    x = synth.normal_tensor(rng, (M, K), torch.bfloat16)
+    ws_host = [(synth.normal_tensor(rng, (n, K), torch.float32) * K ** -0.5).to(torch.bfloat16) for n in feats]
+    ys = [torch.full((M, n), float("nan"), dtype=torch.bfloat16, device="cuda") for n in feats]
+    scratch = B.workspace(B.tr_linear_workspace_size(M, feats, K))
+    B.tr_linear(x.cuda(), [w.cuda() for w in ws_host], ys, scratch)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for w, y in zip(ws_host, ys):
+        want = oracle.linear(H.bits(x), H.bits(w))
+        got = H.to_f64(y)
+        assert np.isfinite(got).all()
+        err = np.abs(got - want)
+        assert (err <= 2.0 ** -8 * np.abs(want) + 1e-3).all(), "max abs err %.3e" % err.max()
+        worst = max(worst, float(err.max()))
+    print("linear %s: max abs err %.3e, slices of k: %d" % ((M, feats, K), worst, B.tr_linear_workspace_size(M, feats, K) // max(1, M * sum(feats) * 4)))
