@@ -50,15 +50,19 @@ constexpr int lin_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 
 template <int N> __device__ __forceinline__ void lin_wait_vm() { __builtin_amdgcn_s_waitcnt(lin_vmcnt_imm(N)); }
 
 template <int MT> constexpr int lin_slot_bytes() { return (4 + MT) * 32 * LIN_ROW; }    // four waves' w pieces, then x
-template <int MT> constexpr int lin_slots() { return MT <= 2 ? 3 : 2; }                  // chunks in flight (<= 144 KB of LDS)
+// Chunks in flight per workgroup.  A small weight (the attention projections) is over within a few round trips, so
+// one workgroup per CU requests its whole slice at once (DEEP: three chunks, two from 96 rows of x on, <= 144 KB of
+// LDS).  A large weight (an MLP's) streams better with one chunk per workgroup and three workgroups per CU.
+template <int MT, bool DEEP> constexpr int lin_slots() { return !DEEP ? 1 : (MT <= 2 ? 3 : 2); }
+constexpr int64_t LIN_LARGE_WEIGHT_BYTES = 64ll << 20;
 
 // MT: 32-row blocks of x (ceil(M / 32), 1..4)
-template <int MT>
+template <int MT, bool DEEP>
 __global__ __launch_bounds__(256) void linear_kernel(const TrLinearArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
     LDS_AS char* lds = (LDS_AS char*)lds_raw;
-    constexpr int NSLOT = lin_slots<MT>(), SLOT = lin_slot_bytes<MT>();
+    constexpr int NSLOT = lin_slots<MT, DEEP>(), SLOT = lin_slot_bytes<MT>();
     constexpr int IPC = 8 + 2 * MT; // load instructions per wave and chunk: its 8 KB of w, its quarter of x
     const int groups = (a.N / 32 + 3) / 4;                      // workgroups along the features
     const int group = blockIdx.x % groups, split = blockIdx.x / groups;
@@ -184,13 +188,15 @@ __global__ __launch_bounds__(256) void linear_combine_kernel(const TrLinearArgs 
 
 } // namespace
 
-// k-slices across workgroups: a workgroup's buffers fill most of a CU's LDS, so at most one is resident per CU; about
-// 200 workgroups measured best (more slices cost more partial traffic and shorter streams than the last CUs gain),
-// and at least two 128-value chunks of k in each
+// k-slices across workgroups.  Small weights: one workgroup per CU, about 200 of them measured best (more slices
+// cost more partial traffic and shorter streams than the last CUs gain).  Large weights: about 450 workgroups, up
+// to three per CU.  At least two 128-value chunks of k in each.
+static bool lin_large(int32_t N, int32_t K) { return (int64_t)N * K * 2 >= LIN_LARGE_WEIGHT_BYTES; }
+
 int tr_linear_splits(int32_t N, int32_t K)
 {
     const int groups = (N / 32 + 3) / 4, chunks = (K + LIN_CK - 1) / LIN_CK;
-    int n_split = (200 + groups / 2) / groups;
+    int n_split = ((lin_large(N, K) ? 450 : 200) + groups / 2) / groups;
     if (n_split > chunks / 2) n_split = chunks / 2;
     if (n_split > 16) n_split = 16;
     if (const char* e = getenv("TR_LIN_SPLIT")) { if (atoi(e) >= 1 && atoi(e) <= chunks) n_split = atoi(e); } // tuning aid
@@ -198,11 +204,11 @@ int tr_linear_splits(int32_t N, int32_t K)
     return n_split;
 }
 
-template <int MT>
+template <int MT, bool DEEP>
 static int launch_linear_mt(const TrLinearArgs& a, hipStream_t s)
 {
-    auto kern = linear_kernel<MT>;
-    constexpr int lds = lin_slots<MT>() * lin_slot_bytes<MT>();
+    auto kern = linear_kernel<MT, DEEP>;
+    constexpr int lds = lin_slots<MT, DEEP>() * lin_slot_bytes<MT>();
     static bool configured = false;
     if (!configured) {
         TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
@@ -235,11 +241,12 @@ int tr_launch_linear(const void* x, int32_t n_out, const void* const* w, void* c
     a.K = K;
     a.n_split = tr_linear_splits(N, K);
     int rc;
+    const bool deep = !lin_large(N, K);
     switch ((M + 31) / 32) {
-    case 1: rc = launch_linear_mt<1>(a, s); break;
-    case 2: rc = launch_linear_mt<2>(a, s); break;
-    case 3: rc = launch_linear_mt<3>(a, s); break;
-    default: rc = launch_linear_mt<4>(a, s); break;
+    case 1: rc = deep ? launch_linear_mt<1, true>(a, s) : launch_linear_mt<1, false>(a, s); break;
+    case 2: rc = deep ? launch_linear_mt<2, true>(a, s) : launch_linear_mt<2, false>(a, s); break;
+    case 3: rc = deep ? launch_linear_mt<3, true>(a, s) : launch_linear_mt<3, false>(a, s); break;
+    default: rc = deep ? launch_linear_mt<4, true>(a, s) : launch_linear_mt<4, false>(a, s); break;
     }
     if (rc) return rc;
     if (a.n_split > 1) {
