@@ -41,7 +41,7 @@ struct TrCopyDesc {
     int32_t delta;
     int32_t blk_start; // first block of the grid that works on this run
 };
-#define TR_MAX_COPY_DESC 128
+#define TR_MAX_COPY_DESC 168 // what the 4 KB argument block holds
 // optional tail of an assemble launch: one request's query tokens appended by the blocks from first_block on
 struct TrAppendTail {
     const void* k_new;

@@ -321,11 +321,12 @@ def test_decode_full_batch64_kv4k(B):
 
 
 def test_more_requests_than_one_launch_describes(B):
-    """70 requests: the request descriptors travel in the kernel arguments, 64 per launch, so this takes two launches of
-    each kernel; once as a decode batch, once as a batched prefill with short queries."""
+    """70 requests x 3 chunks: the descriptors travel in the kernel arguments (64 requests per attention launch, 168 chunk
+    runs per assemble launch, 128 requests per append launch), so the attention and the assemble each take two launches;
+    once as a decode batch, once as a batched prefill with short queries."""
     for n_q_hi, decode in ((1, True), (6, False)):
         cfg = synth.scaled(synth.CONFIGS[3], store_chunks=30, chunk_len_lo=5, chunk_len_hi=60, n_requests=70,
-                           chunks_per_request=2, n_q_lo=1, n_q_hi=n_q_hi)
+                           chunks_per_request=3, n_q_lo=1, n_q_hi=n_q_hi)
         store = synth.make_store(cfg)
         sd = _store_dev(B, cfg.shape, store)
         reqs = synth.make_requests(cfg, store)
