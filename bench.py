@@ -32,10 +32,11 @@ N_VARIANTS = 16
 MEASURED_TRAFFIC = {
     ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 23833624,       # prefix_attn 16.5 MB (6.2 MB of split partials written) + combine 7.3 MB
     ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16961808,
-    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268702313,
+    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268702185,
     ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174881462,  # prefix_attn 154.9 MB + combine 20.0 MB
-    ("tr_chunk_prefill_attn", "offline-64x512"): 808676634,    # table 0.6 MB + key rotation 135.7 MB + attention 672.4 MB
-    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537986694,
+    ("tr_chunk_prefill_attn", "offline-64x512"): 808601553,    # table 0.6 MB + key rotation 135.7 MB + attention 672.4 MB
+    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537986342,
+    ("tr_linear", "qwen2-7b-output-projection-64-tokens"): 42903464,   # linear_kernel 36.0 MB (6.4 MB of partial sums written) + merge 6.9 MB
 }
 
 
@@ -80,7 +81,7 @@ def main():
                          "run so that its slow launches of the same kernels do not blur the kernel trace)")
     ap.add_argument("--case", default=None,
                     help="profiling aid: run only one kernel path --iters times, eagerly, and print nothing but a note "
-                         "(step2, assemble2, attn2, assemble4, attn4, offline5, decode2, copy)")
+                         "(step2, assemble2, attn2, assemble4, attn4, offline5, decode2, linear2, copy)")
     ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -239,7 +240,8 @@ def main():
         roof_extra += bench_decode(torch, B, synth, hbm_roof)
         if args.host_store:
             roof_extra += bench_host_store(torch, B, synth, acct)
-        result["layer_context"] = bench_layer_context(torch, B, synth)
+        result["layer_context"], lin_roofs = bench_layer_context(torch, B, synth, hbm_roof)
+        roof_extra += lin_roofs
         result["hbm_copy_ceiling_gbs"] = measured_copy_rate(torch)
         result["cpu_baseline"] = cpu_baseline(synth, cfg)
     result["roofline_extra"] = roof_extra
@@ -256,6 +258,19 @@ def run_case(torch, B, synth, case, iters):
             dst.copy_(src)
         torch.cuda.synchronize()
         print("case copy: %d launches of a %d-byte device copy" % (iters, src.numel()))
+        return
+    if case == "linear2":
+        # the query projection of configuration 2's layer: 64 tokens, 3584 x 3584 weight
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(3)
+        rnd = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        x, w = rnd(64, 3584), rnd(3584, 3584)
+        y = torch.empty((64, 3584), dtype=torch.bfloat16, device="cuda")
+        ws = B.workspace(B.tr_linear_workspace_size(64, [3584], 3584))
+        for _ in range(iters):
+            B.tr_linear(x, w, y, ws)
+        torch.cuda.synchronize()
+        print("case linear2: %d calls" % iters)
         return
     if case == "decode2":
         run, _ = _decode_setup(torch, B, synth)
@@ -441,7 +456,7 @@ def bench_sequence(torch, B, synth, acct, mfma_roof):
     return [r]
 
 
-def bench_layer_context(torch, B, synth):
+def bench_layer_context(torch, B, synth, hbm_roof):
     """The attention block of one layer around the step: query/key/value projections of the query tokens' hidden
     states (Eq. 1), the step (assemble and append + prefill attention), the output projection, at the Qwen2-7B shape
     with random weights; biases, norms and the MLP are not part of it.  Two workloads: configuration 2, and the shape
@@ -454,7 +469,7 @@ def bench_layer_context(torch, B, synth):
     rnd = lambda *shape, scale=1.0: (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * scale).to(torch.bfloat16)
     wq, wo = rnd(hidden, hidden, scale=hidden ** -0.5), rnd(hidden, hidden, scale=hidden ** -0.5)   # [out_features, in_features]
     wk, wv = (rnd(sh.n_kv_heads * sh.head_dim, hidden, scale=hidden ** -0.5) for _ in range(2))
-    rows = []
+    rows, roofs = [], []
     for name, n_chunks, n_q in (("qwen2-7b-8x512-q64", 8, 64), ("table4-shape-16x512-q128", 16, 128)):
         n_store = 64
         ks, vs = rnd(n_store * 512, sh.n_kv_heads, sh.head_dim), rnd(n_store * 512, sh.n_kv_heads, sh.head_dim)
@@ -499,6 +514,12 @@ def bench_layer_context(torch, B, synth):
         t_lib = _time_calls(torch, layer_library, 20)
         t_step = _time_calls(torch, step, 20)
         t_proj = _time_calls(torch, projections, 20)
+        if n_q == 64:   # roofline rows for the two launches: weights, x and y moved once
+            n_qkv = wq.shape[0] + wk.shape[0] + wv.shape[0]
+            t_qkv = _time_calls(torch, lambda: B.tr_linear(x, [wq, wk, wv], [q, kq, vq], ws_qkv), 20)
+            t_o = _time_calls(torch, lambda: B.tr_linear(att.view(n_q, hidden), wo, o, ws_o), 20)
+            roofs.append(hbm_roof("tr_linear", "qwen2-7b-qkv-projection-64-tokens", 2 * (n_qkv * hidden + n_q * hidden + n_q * n_qkv), t_qkv))
+            roofs.append(hbm_roof("tr_linear", "qwen2-7b-output-projection-64-tokens", 2 * (hidden * hidden + 2 * n_q * hidden), t_o))
         w_bytes = 2 * (wq.numel() + wk.numel() + wv.numel() + wo.numel())
         rows.append({"workload": name, "attention_block_us": round(t_layer[0], 2), "step_us": round(t_step[0], 2),
                      "tr_linear_us": round(t_proj[0], 2), "weight_bytes": w_bytes,
@@ -506,7 +527,7 @@ def bench_layer_context(torch, B, synth):
                      "attention_block_with_library_gemms_us": round(t_lib[0], 2)})
     return {"what": "attention block of one layer: q/k/v projection (tr_linear, one launch for the three weights, random weights) + "
                     "step + output projection (tr_linear); the same block with torch.matmul for the projections beside it",
-            "rows": rows}
+            "rows": rows}, roofs
 
 
 DECODE_BATCH, DECODE_KV = 64, 4096
