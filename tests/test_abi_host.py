@@ -420,7 +420,7 @@ def test_linear_validation(L):
     qkv, qkv_p = _i32([3584, 512, 512])
     fused = L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(3), qkv_p, C.c_int32(3584))
     assert fused % (64 * 4608 * 4) == 0 and fused > 0                # slices of all three outputs side by side
-    big, big_p = _i32([32768])
+    big, big_p = _i32([131072])
     assert L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), big_p, C.c_int32(3584)) == 0   # enough row tiles: no slicing
     bad, bad_p = _i32([3600])
     assert L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), bad_p, C.c_int32(3584)) == 0   # invalid shape: 0
