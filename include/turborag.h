@@ -2,10 +2,15 @@
  * turborag.h - C ABI of the MI355X (gfx950) TurboRAG online-prefill library.
  *
  * The library implements the data-parallel hot path of TurboRAG (arXiv 2410.07590):
- *   Sec. 3.4 step 5  contextual KV-cache formation  -> tr_plan, tr_kv_assemble[_batched], tr_kv_append[_batched]
- *   Sec. 3.4 step 6  KV-cache prefill of the query   -> tr_prefill_attn[_batched]
+ *   Sec. 3.4 step 5  contextual KV-cache formation  -> tr_plan, tr_kv_assemble[_batched], tr_kv_append[_batched],
+ *                                                       tr_kv_assemble_append, tr_kv_assemble_raw
+ *   Sec. 3.4 step 6  KV-cache prefill of the query   -> tr_prefill_attn[_batched], tr_prefill_attn_gather
+ *   Sec. 3.4 step 7  one new token per request        -> tr_decode_attn
  *   Sec. 3.4 step 2  offline document prefill (attention part, independent attention of Sec. 3.2)
  *                                                     -> tr_chunk_prefill_attn
+ *   Sec. 3.3         documents and query in one pass with the masks and position ids of inference
+ *                                                     -> tr_sequence_plan, tr_sequence_prefill_attn
+ *   Eq. 1            projections around the attention for the query tokens -> tr_linear
  *
  * Conventions (all entry points):
  *   - Tensors are token-major, contiguous: [rows, heads, head_dim], element type `tr_shape.dtype`
@@ -19,7 +24,8 @@
  *     nothing has been enqueued.
  *   - Every function returns a tr_status (0 = TR_OK, negative = error).  tr_last_error() returns a
  *     thread-local message for the last error on the calling thread.  Nothing throws, aborts or prints.
- *   - Results are deterministic: same inputs, same bits (no atomics in any reduction).
+ *   - Results are deterministic: same inputs, same bits (no atomics in any reduction).  How a launch is cut into
+ *     workgroups depends only on the shapes and lengths passed in (and, for tuning, on TR_* environment variables).
  *   - RoPE follows Eq. 3: pair m of a head is turned by pos * theta_m, theta_m = rope_base^(-2m/head_dim).
  *     TR_ROPE_INTERLEAVED: pair m = channels (2m, 2m+1), the layout Eq. 3 prints.  TR_ROPE_HALF: pair m =
  *     channels (m, m + head_dim/2), the layout in which the released weights of the models of Sec. 4 keep
