@@ -664,3 +664,69 @@ def test_linear_against_fp64_matmul(B, case):
         assert (err <= 2.0 ** -8 * np.abs(want) + 1e-3).all(), "max abs err %.3e" % err.max()
         worst = max(worst, float(err.max()))
     print("linear %s: max abs err %.3e, slices of k: %d" % ((M, feats, K), worst, B.tr_linear_workspace_size(M, feats, K) // max(1, M * sum(feats) * 4)))
+
+
+# ---- seeded random shapes: group sizes, head dims, layouts, ragged lengths, all four attention entry points -------------
+def _random_case(seed):
+    rng = np.random.Generator(np.random.PCG64([777, seed]))
+    g = int(rng.choice([1, 2, 3, 4, 7, 8, 16]))
+    hkv = int(rng.choice([1, 2, 4, 5]))
+    d = int(rng.choice([64, 128]))
+    layout = int(rng.integers(0, 2))
+    base = float(rng.choice([1e4, 5e5, 1e6]))
+    sh = synth.Shape(g * hkv, hkv, d, "bf16", base, layout)
+    n_store = int(rng.integers(1, 7))
+    lens = [int(x) for x in rng.integers(0, 140, n_store)]
+    n_ids = int(rng.integers(0, 6))
+    ids = rng.integers(0, n_store, n_ids).astype(np.int32)
+    n_q = int(rng.integers(1, 70))
+    mode = int(rng.integers(0, 2))
+    return rng, sh, lens, ids, n_q, mode
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_requests(B, seed):
+    """Random GQA groups (1 .. 16), KV head counts (also odd ones), head dims, RoPE layouts and bases, chunk lengths from 0
+    to 139, 0 .. 5 retrieved chunks with repeats, 1 .. 69 query tokens: assembled path (bit-exact cache), gather path,
+    and the last query token again as a decode step."""
+    rng, sh, lens, ids, n_q, mode = _random_case(seed)
+    row_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rows = max(int(row_start[-1]), 1)
+    store = synth.Store(synth.normal_tensor(rng, (rows, sh.n_kv_heads, sh.head_dim), sh.torch_dtype),
+                        synth.normal_tensor(rng, (rows, sh.n_kv_heads, sh.head_dim), sh.torch_dtype), row_start)
+    sd = _store_dev(B, sh, store)
+    sel = [lens[c] for c in ids]
+    q_pos = (synth.query_start(mode, sel) + np.arange(n_q)).astype(np.int32)
+    req = synth.Request(ids, mode, n_q, synth.normal_tensor(rng, (n_q, sh.n_q_heads, sh.head_dim), sh.torch_dtype),
+                        synth.normal_tensor(rng, (n_q, sh.n_kv_heads, sh.head_dim), sh.torch_dtype),
+                        synth.normal_tensor(rng, (n_q, sh.n_kv_heads, sh.head_dim), sh.torch_dtype), q_pos, sum(sel), sel)
+    err, _ = H.check_request(B, sh, store, sd, req)
+    err_g = H.check_request_gather(B, sh, store, sd, req)
+    # decode: the last query token over the cache the request left behind
+    g = H.run_request_gpu(B, sh, sd, req)
+    gs = H.gpu_shape(B, sh)
+    kv = np.array([0, g["kv_len"]], np.int64)
+    dec = torch.full((1, sh.n_q_heads, sh.head_dim), float("nan"), dtype=sh.torch_dtype, device="cuda")
+    B.tr_decode_attn(gs, req.q[-1:].cuda(), g["cache_k"].cuda(), g["cache_v"].cuda(), torch.from_numpy(q_pos[-1:]).cuda(), kv, dec,
+                     B.workspace(B.tr_decode_attn_workspace_size(gs, kv)))
+    torch.cuda.synchronize()
+    o = H.run_request_oracle(sh, store, req, rows=np.array([n_q - 1], np.int32))
+    err_d = float(np.abs(H.to_f64(dec) - o["out"]).max())
+    assert err_d <= H.BF16_TOL, err_d
+    print("random %d: %s lens %s ids %s n_q %d mode %d: err %.2e gather %.2e decode %.2e" % (seed, sh, lens, list(ids), n_q, mode, err, err_g, err_d))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_sequences(B, seed):
+    """Random shapes through the one-pass entry point (host copy on: the planner decides) and the offline entry point."""
+    rng, sh, lens, _, n_tail, mode = _random_case(100 + seed)
+    lens = tuple(l for l in lens if l > 0)
+    err = _check_sequence(B, sh, lens, n_tail, mode, 900 + seed)
+    if lens:
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        T = int(cu[-1])
+        pc = synth.PackedChunks(synth.normal_tensor(rng, (T, sh.n_q_heads, sh.head_dim), sh.torch_dtype),
+                                synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype),
+                                synth.normal_tensor(rng, (T, sh.n_kv_heads, sh.head_dim), sh.torch_dtype), cu)
+        err = max(err, _check_offline(B, sh, pc)[0])
+    print("random sequence %d: %s lens %s tail %d mode %d: err %.2e" % (seed, sh, lens, n_tail, mode, err))
