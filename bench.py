@@ -35,8 +35,8 @@ MEASURED_TRAFFIC = {
     ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268702185,
     ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174881462,  # prefix_attn 154.9 MB + combine 20.0 MB
     ("tr_chunk_prefill_attn", "offline-64x512"): 808601553,    # table 0.6 MB + key rotation 135.7 MB + attention 672.4 MB
-    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537986342,
-    ("tr_linear", "qwen2-7b-output-projection-64-tokens"): 42903464,   # linear_kernel 36.0 MB (6.4 MB of partial sums written) + merge 6.9 MB
+    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537988070,
+    ("tr_linear", "qwen2-7b-output-projection-64-tokens"): 42858412,   # linear_kernel 35.9 MB (6.4 MB of partial sums written) + merge 6.9 MB
 }
 
 

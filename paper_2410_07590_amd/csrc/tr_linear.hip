@@ -2,14 +2,16 @@
 // query tokens of a request: y[m, n] = sum_k x[m, k] w[n, k] with at most 128 rows of x.  With so few rows the
 // product is bound by streaming the weights once from HBM, so the kernel is organised around that stream.
 //   * A workgroup owns 128 output features (four waves x 32 rows of w, each row contiguous along k) and a slice of k.
-//   * k is walked in chunks of 128 values.  Every wave fetches its 32 x 256-byte piece of w with loads that read whole
-//     256-byte runs, parks it in a wave-private LDS buffer (16-byte pieces XOR-swizzled by the row) and reads it back
-//     in the matrix instruction's operand layout; reading w straight in operand layout would touch 32 rows x 32 bytes
-//     per instruction, which the memory system serves at a fraction of its rate.
+//   * k is walked in chunks of 128 values.  Every wave fetches its 32 x 256-byte piece of w with direct global -> LDS
+//     loads that read whole 256-byte runs (16-byte pieces XOR-swizzled by the row on the source side) and reads it
+//     back in the matrix instruction's operand layout; reading w straight in operand layout would touch 32 rows x
+//     32 bytes per instruction, which the memory system serves at a fraction of its rate.
 //   * The chunk of x (all rows x 256 bytes) is fetched once per workgroup the same way and shared by the four waves:
 //     x is re-read once per 128 features, not once per 32.
-//   * v_mfma_f32_32x32x16_bf16 with w rows as the A operand and x rows as the B operand makes the arithmetic free.
-//   * The next chunk of w and x is in flight (in registers) while the current one is multiplied.
+//   * v_mfma_f32_32x32x16_bf16 with w rows as the A operand and x rows as the B operand makes the arithmetic free,
+//     provided its operand reads are batched ahead of it: read-wait-multiply per step left the products of a chunk
+//     as one chain of LDS latencies, which showed as soon as x had more than 32 rows.
+//   * Up to three chunks per workgroup are in flight in a ring of LDS slots while the current one is multiplied.
 // Slices of k that live in different workgroups write fp32 partial sums that a second small kernel adds in a fixed
 // order: no atomics, same inputs, same bits.
 #include "tr_internal.h"
@@ -40,6 +42,7 @@ struct TrLinearArgs {
 constexpr int LIN_CK = 128;           // values of k per chunk: 256 bytes of every row
 constexpr int LIN_PPR = LIN_CK / 8;   // 16-byte pieces per row of a chunk: 16
 constexpr int LIN_ROW = LIN_CK * 2;   // bytes per parked row
+constexpr int LIN_MAX_SPLIT = 16;     // k-slices across workgroups, at most
 
 #define LDS_AS __attribute__((address_space(3)))
 
@@ -124,16 +127,36 @@ __global__ __launch_bounds__(256) void linear_kernel(const TrLinearArgs a)
         LDS_AS const char* wb = slot + wave * (32 * LIN_ROW);
         LDS_AS const char* xb0 = slot + 4 * 32 * LIN_ROW;
         const int steps = min(LIN_CK, a.K - (c0 + t) * LIN_CK) / 16;
+        auto step = [&](int s) {
+            const bf16x8 wa = *(LDS_AS const bf16x8*)(wb + lin_piece_off(r, 2 * s + h));
 #pragma unroll
-        for (int s = 0; s < LIN_CK / 16; ++s)
-            if (s < steps) { // workgroup-uniform
-                const bf16x8 wa = *(LDS_AS const bf16x8*)(wb + lin_piece_off(r, 2 * s + h));
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const bf16x8 xb = *(LDS_AS const bf16x8*)(xb0 + lin_piece_off(32 * mt + r, 2 * s + h));
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xb, acc[mt], 0, 0, 0);
-                }
+            for (int mt = 0; mt < MT; ++mt) {
+                const bf16x8 xb = *(LDS_AS const bf16x8*)(xb0 + lin_piece_off(32 * mt + r, 2 * s + h));
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xb, acc[mt], 0, 0, 0);
             }
+        };
+        if (steps == LIN_CK / 16) { // a whole chunk: the operands of SB steps are read before their products start
+            constexpr int SB = 2; // deeper batches measured the same and cost registers
+#pragma unroll
+            for (int s0 = 0; s0 < LIN_CK / 16; s0 += SB) {
+                bf16x8 wa[SB], xb[MT][SB];
+#pragma unroll
+                for (int s = 0; s < SB; ++s) {
+                    wa[s] = *(LDS_AS const bf16x8*)(wb + lin_piece_off(r, 2 * (s0 + s) + h));
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) xb[mt][s] = *(LDS_AS const bf16x8*)(xb0 + lin_piece_off(32 * mt + r, 2 * (s0 + s) + h));
+                }
+                __builtin_amdgcn_sched_barrier(0); // keep the reads above: the scheduler would sink each to its use
+#pragma unroll
+                for (int s = 0; s < SB; ++s)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[s], xb[mt][s], acc[mt], 0, 0, 0);
+            }
+        } else {                    // the short last chunk of a row (workgroup-uniform)
+#pragma unroll
+            for (int s = 0; s < LIN_CK / 16; ++s)
+                if (s < steps) step(s);
+        }
         if (t + NSLOT < n_chunks) {
             __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): this wave's operand reads of the slot are done
             __builtin_amdgcn_s_barrier();        // ... and everyone else's: the slot can be refilled
@@ -174,12 +197,18 @@ __global__ __launch_bounds__(256) void linear_combine_kernel(const TrLinearArgs 
     const int m = (int)(4 * i / a.N), n = (int)(4 * i % a.N);
     int j = 0;
     while (j + 1 < a.n_out && n >= 32 * a.tile0[j + 1]) ++j;
-    f32x4 s = *(const f32x4*)(a.partial + 4 * i);
-    for (int sp = 1; sp < a.n_split; ++sp) {
-        const f32x4 t = *(const f32x4*)(a.partial + (int64_t)sp * a.M * a.N + 4 * i);
+    // every slice's load is issued before the first sum needs one: the latencies overlap instead of adding up
+    f32x4 t[LIN_MAX_SPLIT];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) s[e] += t[e];
-    }
+    for (int sp = 0; sp < LIN_MAX_SPLIT; ++sp)
+        if (sp < a.n_split) t[sp] = *(const f32x4*)(a.partial + (int64_t)sp * a.M * a.N + 4 * i);
+    f32x4 s = t[0];
+#pragma unroll
+    for (int sp = 1; sp < LIN_MAX_SPLIT; ++sp)
+        if (sp < a.n_split) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] += t[sp][e];
+        }
     bf16x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = (__bf16)s[e];
@@ -198,8 +227,8 @@ int tr_linear_splits(int32_t N, int32_t K)
     const int groups = (N / 32 + 3) / 4, chunks = (K + LIN_CK - 1) / LIN_CK;
     int n_split = ((lin_large(N, K) ? 450 : 200) + groups / 2) / groups;
     if (n_split > chunks / 2) n_split = chunks / 2;
-    if (n_split > 16) n_split = 16;
-    if (const char* e = getenv("TR_LIN_SPLIT")) { if (atoi(e) >= 1 && atoi(e) <= chunks) n_split = atoi(e); } // tuning aid
+    if (n_split > LIN_MAX_SPLIT) n_split = LIN_MAX_SPLIT;
+    if (const char* e = getenv("TR_LIN_SPLIT")) { if (atoi(e) >= 1 && atoi(e) <= chunks && atoi(e) <= LIN_MAX_SPLIT) n_split = atoi(e); } // tuning aid
     if (n_split < 1) n_split = 1;
     return n_split;
 }
