@@ -638,14 +638,15 @@ def test_half_layout_offline_and_one_pass(B, dtype):
 
 # ---- projections around the attention (Eq. 1), query tokens only ------------------------------------------------------
 LINEAR_CASES = [(64, (3584,), 3584), (128, (3584, 512, 512), 3584), (1, (512,), 3584), (37, (96,), 48), (100, (32,), 16),
-                (128, (18944,), 3584), (33, (64, 32, 32, 64), 2048), (64, (3584,), 18944)]
+                (128, (18944,), 3584), (33, (64, 32, 32, 64), 2048), (64, (3584,), 18944),
+                (40, (4096,), 3136), (65, (160,), 400), (96, (256, 32), 1040)]
 
 
 @pytest.mark.parametrize("case", range(len(LINEAR_CASES)))
 def test_linear_against_fp64_matmul(B, case):
     """y_j = x W_j^T at the Qwen2-7B projection sizes (hidden 3584: query, key and value weights in one launch, the
     output projection, the key rows alone, the MLP's two sizes) and at ragged small ones (rows not a multiple of 32,
-    one k-step, one row tile, four outputs).  Bar: one bf16 rounding of a value accumulated in fp32,
+    one k-step, one row tile, four outputs, rows of k that end in a short chunk after whole ones, three row blocks).  Bar: one bf16 rounding of a value accumulated in fp32,
     |err| <= 2^-8 |y| + 1e-3."""
     M, feats, K = LINEAR_CASES[case]
     rng = np.random.Generator(np.random.PCG64([500, case]))
