@@ -242,6 +242,7 @@ def main():
             roof_extra += bench_host_store(torch, B, synth, acct)
         result["layer_context"], lin_roofs = bench_layer_context(torch, B, synth, hbm_roof)
         roof_extra += lin_roofs
+        result["table4_batch_scaling"] = bench_table4_batches(torch, B, synth)
         result["hbm_copy_ceiling_gbs"] = measured_copy_rate(torch)
         result["cpu_baseline"] = cpu_baseline(synth, cfg)
     result["roofline_extra"] = roof_extra
@@ -528,6 +529,45 @@ def bench_layer_context(torch, B, synth, hbm_roof):
     return {"what": "attention block of one layer: q/k/v projection (tr_linear, one launch for the three weights, random weights) + "
                     "step + output projection (tr_linear); the same block with torch.matmul for the projections beside it",
             "rows": rows}, roofs
+
+
+def bench_table4_batches(torch, B, synth):
+    """The step at the shape of the paper's Table 4 (8192 document tokens = 16 chunks x 512, 128 query tokens per
+    request, Qwen2-7B heads) for batches of 1, 2, 4 and 8 requests, one launch per stage for the whole batch, the
+    store resident on the device (the table's "w/o h2d" column; --host-store times the transfer)."""
+    sh = synth.QWEN2_7B
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20241010)
+    rnd = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    n_store, n_chunks, n_q = 256, 16, 128
+    sd = B.Store(gs, rnd(n_store * 512, sh.n_kv_heads, sh.head_dim), rnd(n_store * 512, sh.n_kv_heads, sh.head_dim),
+                 np.arange(n_store + 1, dtype=np.int64) * 512)
+    rng = np.random.default_rng(11)
+    rows = []
+    for batch in (1, 2, 4, 8):
+        ids = np.concatenate([rng.permutation(n_store)[:n_chunks] for _ in range(batch)]).astype(np.int32)
+        cu_chunks = (np.arange(batch + 1) * n_chunks).astype(np.int32)
+        modes = np.full(batch, synth.POS_REORDERED, np.int32)
+        kv_len = n_chunks * 512 + n_q
+        crs = (np.arange(batch + 1, dtype=np.int64) * kv_len)
+        cu_q = (np.arange(batch + 1) * n_q).astype(np.int32)
+        ck = torch.empty((batch * kv_len, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
+        cv = torch.empty_like(ck)
+        q, k_q, v_q = rnd(batch * n_q, sh.n_q_heads, sh.head_dim), rnd(batch * n_q, sh.n_kv_heads, sh.head_dim), rnd(batch * n_q, sh.n_kv_heads, sh.head_dim)
+        q_pos = torch.arange(n_chunks * 512, kv_len, dtype=torch.int32, device="cuda").repeat(batch)
+        out = torch.empty_like(q)
+        ws = B.workspace(B.tr_prefill_attn_batched_workspace_size(gs, cu_q, crs))
+
+        def step():
+            B.tr_kv_assemble_batched(sd, ids, cu_chunks, modes, crs, ck, cv)
+            B.tr_kv_append_batched(gs, k_q, v_q, q_pos, cu_q, crs, ck, cv)
+            B.tr_prefill_attn_batched(gs, q, ck, cv, q_pos, cu_q, crs, out, ws)
+
+        t = _time_calls(torch, step, 20)
+        rows.append({"batch": batch, "step_us": round(t[0], 2), "us_per_request": round(t[0] / batch, 2)})
+    return {"what": "step (assemble, append, prefill attention; one layer) at Table 4's shape, 8192 document + 128 query tokens per request",
+            "rows": rows}
 
 
 DECODE_BATCH, DECODE_KV = 64, 4096
