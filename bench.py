@@ -36,6 +36,12 @@ MEASURED_TRAFFIC = {
     ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174881462,  # prefix_attn 154.9 MB + combine 20.0 MB
     ("tr_chunk_prefill_attn", "offline-64x512"): 808601553,    # table 0.6 MB + key rotation 135.7 MB + attention 672.4 MB
     ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537988070,
+    ("tr_kv_assemble_append", "qwen2-7b-8x512-q64"): 17439921,
+    ("tr_kv_assemble_raw", "llama3-8b-32x1024-q256"): 268752804,
+    ("tr_kv_assemble_batched", "batched-serving-16req"): 408274047,
+    ("tr_prefill_attn_batched", "batched-serving-16req"): 330134490,    # prefix_attn 276.7 MB + combine 53.4 MB
+    ("tr_sequence_prefill_attn", "32x1024-chunks-plus-256-query-llama3-8b"): 1085016631,  # key rotation 136.6 MB + attention 928.4 MB + combine 20.0 MB
+    ("tr_linear", "qwen2-7b-qkv-projection-64-tokens"): 51639534,      # linear_kernel 43.9 MB (7.1 MB of partial sums written) + merge 7.7 MB
     ("tr_linear", "qwen2-7b-output-projection-64-tokens"): 42858412,   # linear_kernel 35.9 MB (6.4 MB of partial sums written) + merge 6.9 MB
 }
 
@@ -81,7 +87,8 @@ def main():
                          "run so that its slow launches of the same kernels do not blur the kernel trace)")
     ap.add_argument("--case", default=None,
                     help="profiling aid: run only one kernel path --iters times, eagerly, and print nothing but a note "
-                         "(step2, assemble2, attn2, assemble4, attn4, offline5, decode2, linear2, copy)")
+                         "(step2, assemble2, asmapp2, attn2, assemble4, raw4, attn4, batched3, offline5, sequence4, decode2, linear2, "
+                         "linearqkv2, copy)")
     ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -273,6 +280,33 @@ def run_case(torch, B, synth, case, iters):
         torch.cuda.synchronize()
         print("case linear2: %d calls" % iters)
         return
+    if case == "linearqkv2":
+        # query, key and value projections of configuration 2's layer in one launch: 64 tokens, 3584 + 512 + 512 features
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(4)
+        rnd = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        x, w = rnd(64, 3584), [rnd(3584, 3584), rnd(512, 3584), rnd(512, 3584)]
+        y = [torch.empty((64, wj.shape[0]), dtype=torch.bfloat16, device="cuda") for wj in w]
+        ws = B.workspace(B.tr_linear_workspace_size(64, [3584, 512, 512], 3584))
+        for _ in range(iters):
+            B.tr_linear(x, w, y, ws)
+        torch.cuda.synchronize()
+        print("case linearqkv2: %d calls" % iters)
+        return
+    if case == "batched3":
+        _, _, asm, app, att = _config3_setup(torch, B, synth)
+        for _ in range(iters):
+            asm(); app(); att()
+        torch.cuda.synchronize()
+        print("case batched3: %d iterations of assemble, append, attention" % iters)
+        return
+    if case == "sequence4":
+        run = _sequence_setup(torch, B, synth)[-1]
+        for _ in range(iters):
+            run()
+        torch.cuda.synchronize()
+        print("case sequence4: %d calls" % iters)
+        return
     if case == "decode2":
         run, _ = _decode_setup(torch, B, synth)
         for _ in range(iters):
@@ -314,7 +348,8 @@ def run_case(torch, B, synth, case, iters):
     att = lambda: B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
     asm(); app()
     fused = lambda: B.tr_kv_assemble_append(sd, req.chunk_ids, offsets, req.pos_mode, k_q, v_q, q_pos, ck, cv)
-    what = {"assemble": [asm], "attn": [att], "step": [fused, att]}[case[:-1]]
+    raw = lambda: B.tr_kv_assemble_raw(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
+    what = {"assemble": [asm], "attn": [att], "step": [fused, att], "asmapp": [fused], "raw": [raw]}[case[:-1]]
     for _ in range(iters):
         for f in what:
             f()
@@ -369,7 +404,7 @@ def bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof):
                       t_att, acct.prefill_attn_bytes(req.n_q, kv_len, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb))]
 
 
-def bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof):
+def _config3_setup(torch, B, synth):
     """Batched serving: 16 requests x 10 chunks (bounded Zipf ids over 1000 chunks of 256..1024 rows), 32..128 query
     tokens each, composite and reordered positions mixed; one launch per stage for the whole batch."""
     cfg = synth.CONFIGS[3]
@@ -395,6 +430,12 @@ def bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof):
     asm = lambda: B.tr_kv_assemble_batched(sd, ids, cu_chunks, modes, crs, ck, cv)
     app = lambda: B.tr_kv_append_batched(gs, k_q, v_q, q_pos, cu_q, crs, ck, cv)
     att = lambda: B.tr_prefill_attn_batched(gs, q, ck, cv, q_pos, cu_q, crs, out, ws)
+    return cfg, reqs, asm, app, att
+
+
+def bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof):
+    cfg, reqs, asm, app, att = _config3_setup(torch, B, synth)
+    sh = cfg.shape
     asm(); app()
     t_asm, t_app, t_att = _time_calls(torch, asm, 20), _time_calls(torch, app, 30), _time_calls(torch, att, 30)
     eb = sh.elem_bytes
@@ -430,7 +471,7 @@ def bench_config5(torch, B, synth, acct, mfma_roof):
     return [r]
 
 
-def bench_sequence(torch, B, synth, acct, mfma_roof):
+def _sequence_setup(torch, B, synth):
     """The fine-tuning / whole-prefill form of configuration 4 in one pass: 32 chunks x 1024 tokens that attend
     inside their own chunk, then 256 query tokens that attend everything (reordered position ids)."""
     cfg = synth.CONFIGS[4]
@@ -447,6 +488,11 @@ def bench_sequence(torch, B, synth, acct, mfma_roof):
     seg_d, pos_d = torch.from_numpy(seg).cuda(), torch.from_numpy(pos).cuda()
     ws = B.workspace(B.tr_sequence_prefill_attn_workspace_size(gs, seg, T))
     run = lambda: B.tr_sequence_prefill_attn(gs, q, k, v, seg_d, pos_d, out, k_rot, seg_start_host=seg, workspace=ws)
+    return sh, lens, n_tail, T, run
+
+
+def bench_sequence(torch, B, synth, acct, mfma_roof):
+    sh, lens, n_tail, T, run = _sequence_setup(torch, B, synth)
     t = _time_calls(torch, run, 10)
     n_doc = sum(lens)
     pairs = acct.visible_pairs_blockdiag(lens) + acct.visible_pairs_prefix(n_tail, n_doc + n_tail)
