@@ -29,7 +29,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(_build.build())
+        # TR_ORACLE_LIB: another build of turborag_oracle.c; the test that plants mistakes in copies of the source
+        # and expects the pins to fail runs the pin tests against such a copy
+        _lib = C.CDLL(os.environ.get("TR_ORACLE_LIB") or _build.build())
         _lib.orc_num_threads.restype = C.c_int
     return _lib
 

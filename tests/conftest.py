@@ -6,6 +6,11 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+# a directory that holds another copy of the oracle package: the test that plants mistakes in such copies runs the
+# pin tests against them in child processes
+if os.environ.get("TR_ORACLE_PATH"):
+    sys.path.insert(0, os.environ["TR_ORACLE_PATH"])
+    import oracle  # noqa: F401  (bound now: pytest puts the repository root in front again when it imports the tests)
 
 
 def pytest_configure(config):
