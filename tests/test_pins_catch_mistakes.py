@@ -14,7 +14,9 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "turborag_oracle.c")
 
-# (name, text in the source, what a mistaken author could have written instead)
+# (name, text in the source, what a mistaken author could have written instead); a pair of tuples where the mistake
+# needs a second edit to stay inside its buffers: every planted mistake computes wrong values, none touches memory it
+# does not own, so a failure is a pin's assertion and never a crash
 MISTAKES = [
     ("rotation turns the other way", "y[a] = xa * c - xb * s;\n        y[b] = xb * c + xa * s;", "y[a] = xa * c + xb * s;\n        y[b] = xb * c - xa * s;"),
     ("cos and sin exchanged", "double c = cos(ang), s = sin(ang);", "double c = sin(ang), s = cos(ang);"),
@@ -28,8 +30,7 @@ MISTAKES = [
     ("composite ids run on", "pos[off + t] = (int32_t)((pos_mode == ORC_POS_REORDERED) ? off + t : t);", "pos[off + t] = (int32_t)(off + t);"),
     ("re-rotation offset one chunk late", "delta[i] = (pos_mode == ORC_POS_REORDERED) ? off : 0;", "delta[i] = (pos_mode == ORC_POS_REORDERED) ? off + len : 0;"),
     ("keys turned back instead of forward", "rope_vec(tmp, out_k + dn, d, (double)delta[i], theta, layout);", "rope_vec(tmp, out_k + dn, d, -(double)delta[i], theta, layout);"),
-    ("chunk ids ignored in the gather", "int64_t src0 = row_start[chunk_ids[i]];\n        int64_t len = row_start[chunk_ids[i] + 1] - src0;",
-     "int64_t src0 = row_start[i];\n        int64_t len = row_start[chunk_ids[i] + 1] - row_start[chunk_ids[i]];"),
+    ("rows of a chunk gathered one row late", "int64_t so = ((src0 + t) * n_kv + h) * (int64_t)d;", "int64_t so = ((src0 + (t + 1) % len) * n_kv + h) * (int64_t)d;"),
     ("values re-rotated like keys", "out_v[dn + e] = load_elem(v_store, so + e, dtype);", "out_v[dn + e] = load_elem(k_store, so + e, dtype);"),
     ("score scale dropped", "double scale = 1.0 / sqrt((double)d);", "double scale = 1.0;"),
     ("score scale 1/d", "double scale = 1.0 / sqrt((double)d);", "double scale = 1.0 / (double)d;"),
@@ -37,7 +38,8 @@ MISTAKES = [
     ("query token does not see itself", "0, n_doc + i, scratch", "0, n_doc + i - 1, scratch"),
     ("query token sees its successor", "0, n_doc + i, scratch", "0, (n_doc + i + 1 < kv_len ? n_doc + i + 1 : n_doc + i), scratch"),
     ("query heads dealt round-robin to KV heads", "attend_row(q_rot + ((int64_t)i * n_qh + h) * d, k, v, n_kv, h / g, d,", "attend_row(q_rot + ((int64_t)i * n_qh + h) * d, k, v, n_kv, h % n_kv, d,"),
-    ("documents attend across chunks", "cu[c], t, scratch", "0, t, scratch"),
+    ("documents attend across chunks", ("cu[c], t, scratch", "double* scratch = (double*)malloc(sizeof(double) * (size_t)max_len);"),
+     ("0, t, scratch", "double* scratch = (double*)malloc(sizeof(double) * (size_t)(cu[n_chunks] + 1)); (void)max_len;")),
     ("one-pass mask ignores the range start", "lo[t], t, scratch", "0, t, scratch"),
     ("bf16 by truncation", "double q = nearbyint(ldexp(x, -ulp_exp));", "double q = trunc(ldexp(x, -ulp_exp));"),
     ("bf16 with 7 significant bits", "int ulp_exp = (e - 1) - 7;", "int ulp_exp = (e - 1) - 6;"),
@@ -61,6 +63,14 @@ PY_MISTAKES = [
 ]
 
 
+def _apply(text, name, old, new):
+    olds, news = (old, new) if isinstance(old, tuple) else ((old,), (new,))
+    for o, n in zip(olds, news):
+        assert text.count(o) == 1, "the source text of mistake %r is not unique in the oracle: %d" % (name, text.count(o))
+        text = text.replace(o, n)
+    return text
+
+
 def _build(src_text, path):
     with open(path + ".c", "w") as f:
         f.write(src_text)
@@ -75,6 +85,7 @@ def _pins_pass(where):
     files = sorted(glob.glob(os.path.join(ROOT, "tests", "test_oracle_*.py")))
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "not gpu", *files],
                        cwd=ROOT, env=env, capture_output=True, text=True)
+    assert r.returncode in (0, 1), "the pin tests did not run to an ordinary end (exit %d):\n%s" % (r.returncode, r.stdout[-600:] + r.stderr[-600:])
     return r.returncode == 0, r.stdout[-600:]
 
 
@@ -82,8 +93,7 @@ def test_every_planted_mistake_fails_a_pin(tmp_path):
     src = open(SRC).read()
     libs = []
     for i, (name, old, new) in enumerate(MISTAKES):
-        assert src.count(old) == 1, "the source text of mistake %r is not unique in the oracle: %d" % (name, src.count(old))
-        libs.append(_build(src.replace(old, new), str(tmp_path / ("mistake%02d" % i))))
+        libs.append(_build(_apply(src, name, old, new), str(tmp_path / ("mistake%02d" % i))))
     control = _build(src, str(tmp_path / "control"))
     with ThreadPoolExecutor(4) as ex:
         results = list(ex.map(_pins_pass, libs + [control]))
@@ -98,9 +108,7 @@ def _package_copy(tmp_path, name, old=None, new=None):
     shutil.copytree(os.path.join(ROOT, "oracle"), str(d / "oracle"), ignore=shutil.ignore_patterns("__pycache__"))
     if old is not None:
         f = d / "oracle" / "__init__.py"
-        text = f.read_text()
-        assert text.count(old) == 1, "the source text of mistake %r is not unique in the oracle: %d" % (name, text.count(old))
-        f.write_text(text.replace(old, new))
+        f.write_text(_apply(f.read_text(), name, old, new))
     return str(d)
 
 
