@@ -39,8 +39,8 @@ MEASURED_TRAFFIC = {
     ("tr_kv_assemble_append", "qwen2-7b-8x512-q64"): 17439921,
     ("tr_kv_assemble_raw", "llama3-8b-32x1024-q256"): 268752804,
     ("tr_kv_assemble_batched", "batched-serving-16req"): 408274047,
-    ("tr_prefill_attn_batched", "batched-serving-16req"): 330134490,    # prefix_attn 276.7 MB + combine 53.4 MB
-    ("tr_sequence_prefill_attn", "32x1024-chunks-plus-256-query-llama3-8b"): 1085016631,  # key rotation 136.6 MB + attention 928.4 MB + combine 20.0 MB
+    ("tr_prefill_attn_batched", "batched-serving-16req"): 329371660,    # prefix_attn 275.9 MB + combine 53.4 MB
+    ("tr_sequence_prefill_attn", "32x1024-chunks-plus-256-query-llama3-8b"): 1085821232,  # key rotation 136.6 MB + attention 929.2 MB + combine 20.0 MB
     ("tr_linear", "qwen2-7b-qkv-projection-64-tokens"): 51639534,      # linear_kernel 43.9 MB (7.1 MB of partial sums written) + merge 7.7 MB
     ("tr_linear", "qwen2-7b-output-projection-64-tokens"): 42858412,   # linear_kernel 35.9 MB (6.4 MB of partial sums written) + merge 6.9 MB
 }
