@@ -221,7 +221,11 @@ template <int D> struct Acc {
 };
 
 // Issue this wave's share of the direct global->LDS loads of tile [kt, kt+KROWS) into one stage (K rows, then V rows).
-template <int D, int NW, int KROWS = KT>
+// AUX is the cache policy of the loads: 0 where other workgroups read the same tile soon (the row tiles of a long
+// query), DMA_STREAM (non-temporal) where every key is read exactly once (decode: 114 -> 100 us for 64 x 4096 rows;
+// the same hint on the long-query kernels, whose row tiles share keys through L2, cost 5-8 %).
+constexpr int DMA_STREAM = 2;
+template <int D, int NW, int KROWS = KT, int AUX = 0>
 __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const __bf16* __restrict__ v, int64_t row_elems,
                                            int head_off, int kt, int key_clamp, LDS_AS char* stage, int wave, int lane)
 {
@@ -238,9 +242,9 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const _
         const int ck = pc ^ G::kswz(row);
         const int cv = 4 * ((pc >> 2) ^ G::vswz(row)) + (pc & 3);
         const int64_t base = (int64_t)key * row_elems + head_off;
-        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(k + base + ck * 8), (LDS_AS void*)(stage + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(k + base + ck * 8), (LDS_AS void*)(stage + i * 1024), 16, 0, AUX);
         __builtin_amdgcn_global_load_lds((const GLB_AS void*)(v + base + cv * 8),
-                                         (LDS_AS void*)(stage + KROWS * D * 2 + i * 1024), 16, 0, 0);
+                                         (LDS_AS void*)(stage + KROWS * D * 2 + i * 1024), 16, 0, AUX);
     }
 }
 
@@ -827,7 +831,7 @@ __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPr
     load_q_raw<D>((const __bf16*)a.q, rc, h, raw);
     asm volatile("" : "+v"(th));
     __builtin_amdgcn_sched_barrier(0);
-    if (n_tiles > 0) issue_tile<D, NW, SHORT_KT>(kp, vp, row_elems, head_off, kt_begin, key_clamp, smem, wave, lane);
+    if (n_tiles > 0) issue_tile<D, NW, SHORT_KT, DMA_STREAM>(kp, vp, row_elems, head_off, kt_begin, key_clamp, smem, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
     bf16x8 qf[D / 16];
     {
@@ -863,7 +867,7 @@ __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPr
         wait_vm<0>(); // two stages: tile t is the only load in flight here
         __builtin_amdgcn_s_barrier(); // tile t is in LDS; everyone is done with tile t-1
         if (t + 1 < n_tiles)
-            issue_tile<D, NW, SHORT_KT>(kp, vp, row_elems, head_off, kt + SHORT_KT, key_clamp, smem + ((t + 1) % NS) * STAGE, wave, lane);
+            issue_tile<D, NW, SHORT_KT, DMA_STREAM>(kp, vp, row_elems, head_off, kt + SHORT_KT, key_clamp, smem + ((t + 1) % NS) * STAGE, wave, lane);
         const int ktw = kt + 32 * wave; // this wave's 32 keys
         if (ktw <= wave_hi_max && ktw < kt_end) {
             LDS_AS const char* stage = smem + (t % NS) * STAGE;
