@@ -35,7 +35,7 @@ MEASURED_TRAFFIC = {
     ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268702185,
     ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174881462,  # prefix_attn 154.9 MB + combine 20.0 MB
     ("tr_chunk_prefill_attn", "offline-64x512"): 808601553,    # table 0.6 MB + key rotation 135.7 MB + attention 672.4 MB
-    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537988070,
+    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537985990,
     ("tr_kv_assemble_append", "qwen2-7b-8x512-q64"): 17439921,
     ("tr_kv_assemble_raw", "llama3-8b-32x1024-q256"): 268752804,
     ("tr_kv_assemble_batched", "batched-serving-16req"): 408274047,
