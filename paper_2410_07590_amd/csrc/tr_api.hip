@@ -1117,7 +1117,7 @@ int check_linear(int32_t M, int32_t n_out, const int32_t* n_features, int32_t K,
 }
 size_t linear_ws_bytes(int32_t M, int64_t N, int32_t K)
 {
-    const int n_split = tr_linear_splits((int32_t)N, K);
+    const int n_split = tr_linear_splits(M, (int32_t)N, K);
     return n_split > 1 ? tr_align256((size_t)n_split * M * N * 4) : 0;
 }
 } // namespace

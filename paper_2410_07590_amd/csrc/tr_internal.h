@@ -226,8 +226,8 @@ int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, const TrPrefixArgs* combi
 int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_args, int head_dim, hipStream_t s);
 int tr_launch_blockdiag_attn_f32(const TrBlockDiagArgs& a, int head_dim, hipStream_t s);
 // y_j = x w_j^T for at most 128 rows of x and up to TR_LINEAR_MAX_OUT weights that share x; N = sum of the feature
-// counts; partial: fp32 [tr_linear_splits(N, K), M, N] when that count exceeds 1
+// counts; partial: fp32 [tr_linear_splits(M, N, K), M, N] when that count exceeds 1
 #define TR_LINEAR_MAX_OUT 4
-int tr_linear_splits(int32_t N, int32_t K);
+int tr_linear_splits(int32_t M, int32_t N, int32_t K);
 int tr_launch_linear(const void* x, int32_t n_out, const void* const* w, void* const* y, const int32_t* n_features, void* partial,
                      int32_t M, int32_t K, hipStream_t s);

@@ -37,6 +37,7 @@ struct TrLinearArgs {
     int32_t n_out;
     int32_t M, N, K;
     int32_t n_split;
+    int32_t m_split;                    // 1, or 2: rows [0, 64) and [64, M) of x go to two workgroups of the same XCD
 };
 
 constexpr int LIN_CK = 128;           // values of k per chunk: 256 bytes of every row
@@ -68,7 +69,17 @@ __global__ __launch_bounds__(256) void linear_kernel(const TrLinearArgs a)
     constexpr int NSLOT = lin_slots<MT, DEEP>(), SLOT = lin_slot_bytes<MT>();
     constexpr int IPC = 8 + 2 * MT; // load instructions per wave and chunk: its 8 KB of w, its quarter of x
     const int groups = (a.N / 32 + 3) / 4;                      // workgroups along the features
-    const int group = blockIdx.x % groups, split = blockIdx.x / groups;
+    // With two row halves, blocks b and b + 8 (same XCD, dispatched together) take the two halves of one
+    // (features, k-slice) item, so that the second read of its weights is served by that XCD's L2.
+    int item = blockIdx.x, m0 = 0;
+    if (a.m_split == 2) {
+        item = ((blockIdx.x >> 4) << 3) | (blockIdx.x & 7);
+        m0 = ((blockIdx.x >> 3) & 1) * (32 * MT);
+        if (item >= groups * a.n_split) return;                 // padding of the grid to a multiple of 16 (whole workgroup)
+    }
+    const int M = min(a.M - m0, 32 * MT);                       // rows of x this workgroup multiplies
+    const __bf16* xrows = a.x + (int64_t)m0 * a.K;
+    const int group = item % groups, split = item / groups;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
     const int tile = min(4 * group + wave, a.N / 32 - 1);       // a wave past the last tile redoes it and stores nothing
@@ -102,7 +113,7 @@ __global__ __launch_bounds__(256) void linear_kernel(const TrLinearArgs a)
         for (int i = 0; i < 2 * MT; ++i) {
             const int row = 4 * (wave * 2 * MT + i) + lrow; // this wave's quarter of the 32 MT rows
             const int piece = min(c * LIN_PPR + (ppiece ^ (row & (LIN_PPR - 1))), last_piece);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.x + (int64_t)min(row, a.M - 1) * a.K + 8 * piece),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xrows + (int64_t)min(row, M - 1) * a.K + 8 * piece),
                                              (LDS_AS void*)(xdst + (wave * 2 * MT + i) * 1024), 16, 0, 0);
         }
     };
@@ -168,8 +179,8 @@ __global__ __launch_bounds__(256) void linear_kernel(const TrLinearArgs a)
     // element e of acc[mt] is y_j[32 mt + r][32 ltile + 8 (e >> 2) + 4 h + (e & 3)]
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int m = 32 * mt + r;
-        if (m >= a.M) continue;
+        if (32 * mt + r >= M) continue;
+        const int m = m0 + 32 * mt + r;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int n = 32 * tile + 8 * q4 + 4 * h; // column among all outputs
@@ -220,11 +231,20 @@ __global__ __launch_bounds__(256) void linear_combine_kernel(const TrLinearArgs 
 // k-slices across workgroups.  Small weights: one workgroup per CU, about 200 of them measured best (more slices
 // cost more partial traffic and shorter streams than the last CUs gain).  Large weights: about 450 workgroups, up
 // to three per CU.  At least two 128-value chunks of k in each.
-static bool lin_large(int32_t N, int32_t K) { return (int64_t)N * K * 2 >= LIN_LARGE_WEIGHT_BYTES; }
 
-int tr_linear_splits(int32_t N, int32_t K)
+static bool lin_large(int32_t N, int32_t K) { return (int64_t)N * K * 2 >= LIN_LARGE_WEIGHT_BYTES; }
+// More than 96 rows of x against a small weight: two workgroups per item, one per 64 rows, each with the ring of
+// three chunks that 64 rows leave room for (128 rows x 4608 x 3584: 20.7 -> 18.9 us; at 65..96 rows and for large
+// weights one workgroup per item measured faster).  TR_LIN_MSPLIT=1 keeps one (tuning aid).
+static int lin_m_split(int32_t M, int32_t N, int32_t K)
 {
-    const int groups = (N / 32 + 3) / 4, chunks = (K + LIN_CK - 1) / LIN_CK;
+    if (const char* e = getenv("TR_LIN_MSPLIT")) { if (atoi(e) == 1) return 1; }
+    return (M > 96 && !lin_large(N, K)) ? 2 : 1;
+}
+
+int tr_linear_splits(int32_t M, int32_t N, int32_t K)
+{
+    const int groups = (N / 32 + 3) / 4 * lin_m_split(M, N, K), chunks = (K + LIN_CK - 1) / LIN_CK;
     int n_split = ((lin_large(N, K) ? 450 : 200) + groups / 2) / groups;
     if (n_split > chunks / 2) n_split = chunks / 2;
     if (n_split > LIN_MAX_SPLIT) n_split = LIN_MAX_SPLIT;
@@ -243,8 +263,9 @@ static int launch_linear_mt(const TrLinearArgs& a, hipStream_t s)
         TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         configured = true;
     }
-    const int groups = (a.N / 32 + 3) / 4;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(groups * a.n_split)), dim3(256), lds, s, a);
+    const int items = (a.N / 32 + 3) / 4 * a.n_split;
+    const int blocks = a.m_split == 2 ? 16 * ((items + 7) / 8) : items;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;
 }
@@ -268,10 +289,11 @@ int tr_launch_linear(const void* x, int32_t n_out, const void* const* w, void* c
     a.M = M;
     a.N = N;
     a.K = K;
-    a.n_split = tr_linear_splits(N, K);
+    a.n_split = tr_linear_splits(M, N, K);
+    a.m_split = lin_m_split(M, N, K);
     int rc;
     const bool deep = !lin_large(N, K);
-    switch ((M + 31) / 32) {
+    switch (a.m_split == 2 ? 2 : (M + 31) / 32) {
     case 1: rc = deep ? launch_linear_mt<1, true>(a, s) : launch_linear_mt<1, false>(a, s); break;
     case 2: rc = deep ? launch_linear_mt<2, true>(a, s) : launch_linear_mt<2, false>(a, s); break;
     case 3: rc = deep ? launch_linear_mt<3, true>(a, s) : launch_linear_mt<3, false>(a, s); break;
