@@ -1141,11 +1141,8 @@ int launch_prefix(const TrPrefixArgs& a, hipStream_t s)
 {
     auto kern = prefix_attn_kernel<D, NW, NS, HALF>;
     constexpr int lds = smem_bytes<D, NW, NS>();
-    static bool configured = false;
-    if (!configured) {
-        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    if (int rc = tr_raise_lds_limit((const void*)kern, lds, &configured)) return rc;
     hipLaunchKernelGGL(kern, dim3(a.n_items), dim3(64 * NW), lds, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;
@@ -1158,11 +1155,8 @@ int launch_short(const TrPrefixArgs& a, hipStream_t s)
     constexpr int ring = SHORT_NS * short_stage_bytes<D>();
     constexpr int merge = SHORT_NW * 32 * short_merge_row_bytes<D>() + SHORT_NW * 32 * 8;
     constexpr int lds = ring > merge ? ring : merge;
-    static bool configured = false;
-    if (!configured) {
-        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    if (int rc = tr_raise_lds_limit((const void*)kern, lds, &configured)) return rc;
     hipLaunchKernelGGL(kern, dim3(a.n_items), dim3(64 * SHORT_NW), lds, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;
@@ -1174,11 +1168,8 @@ int launch_gather(const TrGatherArgs& a, hipStream_t s)
     auto kern = gather_attn_kernel<D, HALF>;
     constexpr int staging = GATHER_NW * 32 * (64 * 4 + 16);
     constexpr int lds = gather_lds_bytes<D>() > staging ? gather_lds_bytes<D>() : staging;
-    static bool configured = false;
-    if (!configured) {
-        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    if (int rc = tr_raise_lds_limit((const void*)kern, lds, &configured)) return rc;
     hipLaunchKernelGGL(kern, dim3(a.n_items), dim3(64 * GATHER_NW), lds, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;
@@ -1189,11 +1180,8 @@ int launch_blockdiag(const TrBlockDiagArgs& a, hipStream_t s)
 {
     auto kern = blockdiag_attn_kernel<D, NW, NS, HALF>;
     constexpr int lds = smem_bytes<D, NW, NS>();
-    static bool configured = false;
-    if (!configured) {
-        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    if (int rc = tr_raise_lds_limit((const void*)kern, lds, &configured)) return rc;
     hipLaunchKernelGGL(kern, dim3(a.items_per_head * a.n_kv_heads), dim3(64 * NW), lds, s, a);
     TR_HIP(hipGetLastError());
     return TR_OK;

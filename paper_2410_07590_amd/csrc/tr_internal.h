@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libturborag_hip.so.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stddef.h>
 #include <vector>
@@ -15,6 +16,21 @@ void tr_clear_error();
         hipError_t e__ = (expr);                                                               \
         if (e__ != hipSuccess) return tr_fail(TR_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
     } while (0)
+
+// A kernel that needs more dynamic LDS than the default limit has the limit raised once per device: the attribute
+// belongs to the function on the device that is current, so a process that uses a second device must set it there
+// too.  `done` holds one bit per device ordinal (mod 64) and is safe to race on: the worst case sets it twice.
+static inline int tr_raise_lds_limit(const void* kernel, int bytes, std::atomic<uint64_t>* done)
+{
+    int dev = 0;
+    TR_HIP(hipGetDevice(&dev));
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(done->load(std::memory_order_acquire) & bit)) {
+        TR_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+        done->fetch_or(bit, std::memory_order_release);
+    }
+    return TR_OK;
+}
 
 int tr_check_shape(const tr_shape* s);
 static inline int tr_elem_bytes(const tr_shape* s) { return s->dtype == TR_F32 ? 4 : 2; }

@@ -258,11 +258,8 @@ static int launch_linear_mt(const TrLinearArgs& a, hipStream_t s)
 {
     auto kern = linear_kernel<MT, DEEP>;
     constexpr int lds = lin_slots<MT, DEEP>() * lin_slot_bytes<MT>();
-    static bool configured = false;
-    if (!configured) {
-        TR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    if (int rc = tr_raise_lds_limit((const void*)kern, lds, &configured)) return rc;
     const int items = (a.N / 32 + 3) / 4 * a.n_split;
     const int blocks = a.m_split == 2 ? 16 * ((items + 7) / 8) : items;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, a);
