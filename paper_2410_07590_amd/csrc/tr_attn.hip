@@ -440,27 +440,46 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
     }
 }
 
-// Raw query loads, the first K/V tiles, then the rotation: the tile loads fly while the angles are computed.
-// Every ordinary load is issued before the tile loads, because loads return in order and one issued later
-// would make its consumer wait for the tiles.  pos_lane: position id of token slot (lane & 7) of this wave, loaded by
-// the caller; pos_of_slot serves the later passes of small GQA groups.  The rotation table sits in stage NS-1, which
-// no tile load targets before the first barrier of the tile loop.
+// The ordinary loads of a workgroup's start, issued as one batch before anything waits: the position id of the lane's
+// token slot and whatever indices the caller needs (issued by the caller, first), theta, then the raw query rows.
+// Loads return in order, so the small ones in front are back after one L2 round trip while the query rows are
+// still on their way from HBM.
+template <int D> struct QLoads {
+    double th;          // theta_rev[lane % (D/2)]
+    u32x4 raw[D / 16];  // this lane's raw query fragments
+};
+
+// PINNED: theta is kept in front of the query rows and the batch is closed with a scheduling fence.  That pays where
+// the query rows come from HBM (the offline and one-pass kernels: every row is new); where they sit in L2 (a request's
+// few query tokens, read by every key split) the compiler's own order measured 2 % faster.
+template <int D, bool PINNED>
+__device__ __forceinline__ void issue_q_loads(const __bf16* __restrict__ q, const double* theta_rev, const RowCtx& rc, QLoads<D>& ql)
+{
+    const int lane = threadIdx.x & 63, h = lane >> 5;
+    ql.th = theta_rev[lane % (D / 2)];
+    if (PINNED) __builtin_amdgcn_sched_barrier(0);
+    load_q_raw<D>(q, rc, h, ql.raw);
+    if (PINNED) __builtin_amdgcn_sched_barrier(0);
+}
+
+// The first K/V tiles, then the rotation: the tile loads fly while the angles are computed.  theta is waited for
+// before the tile loads go out (with it pos_lane, the position id of token slot (lane & 7) of this wave, which the
+// caller loaded in front of it): a vector-memory result that is first touched after the tile loads would wait for
+// the tiles as well.  The query rows are touched after the angle table is built; pos_of_slot serves the later passes
+// of small GQA groups.  The rotation table sits in stage NS-1, which no tile load targets
+// before the first barrier of the tile loop.
 template <int D, int NW, int NS, bool HALF, class PosFn>
-__device__ __forceinline__ void prologue(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-                                         const Walk& w, const RowCtx& rc, int pos_lane, int slot, int n_slots, PosFn pos_of_slot,
-                                         const double* theta_rev, float sl2e, LDS_AS char* smem,
+__device__ __forceinline__ void prologue(const __bf16* __restrict__ k, const __bf16* __restrict__ v, const Walk& w, QLoads<D>& ql,
+                                         int pos_lane, int slot, int n_slots, PosFn pos_of_slot, float sl2e, LDS_AS char* smem,
                                          bf16x8 (&qf)[D / 16])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5;
-    double th = theta_rev[lane % (D / 2)];
-    u32x4 raw[D / 16];
-    load_q_raw<D>(q, rc, h, raw);
-    asm volatile("" : "+v"(th));
+    asm volatile("" : "+v"(ql.th));
     __builtin_amdgcn_sched_barrier(0);
     issue_prologue<D, NW, NS>(k, v, w, smem, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
     LDS_AS char* tab = smem + (NS - 1) * Geo<D>::STAGE_BYTES + wave * (ROT_SLOTS * 4 * D);
-    rotate_queries<D, HALF>(raw, tab, th, lane, h, slot, n_slots, sl2e,
+    rotate_queries<D, HALF>(ql.raw, tab, ql.th, lane, h, slot, n_slots, sl2e,
                             [&](int s) { return s < ROT_SLOTS ? pos_lane : pos_of_slot(s); }, qf);
 }
 
@@ -550,6 +569,8 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     const int n_slots = (32 * wave + 31) / g - (32 * wave) / g + 1;
     auto pos_of_slot = [&](int s) { return a.q_pos[sd.q_row0 + min(wave_tok0 + s, sd.n_q - 1)]; };
     const int pos_lane = pos_of_slot(lane & (ROT_SLOTS - 1));
+    QLoads<D> ql;
+    issue_q_loads<D, false>((const __bf16*)a.q, a.theta_rev, rc, ql);
 
     const int first_tok = tile * tpt;
     const int last_tok = min(first_tok + tpt, sd.n_q) - 1;
@@ -558,8 +579,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_attn_kernel(const TrPrefixA
     const Walk w = make_walk(sb, min(se, sd.kv_row0 + n_doc + last_tok + 1), sd.kv_row0 + sd.kv_len - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    prologue<D, NW, NS, HALF>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
-                        a.theta_rev, a.scale_log2e, smem, qf);
+    prologue<D, NW, NS, HALF>((const __bf16*)a.k, (const __bf16*)a.v, w, ql, pos_lane, slot, n_slots, pos_of_slot, a.scale_log2e, smem, qf);
 
     Acc<D> acc;
 #pragma unroll
@@ -1069,24 +1089,36 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     RowCtx rc;
     rc.valid = (rl < tpt * g) && (t < T);
     rc.orow = t * a.n_q_heads + kvh * g + rl % g;
-    rc.key_lo = rc.valid ? chunk_start(a.tok_start, t) : 0;
     rc.key_hi = t;
-    // position id of each token slot of this wave: given, or chunk-local
     const int wave_t0 = tile * tpt + (32 * wave) / g;
+    const int slot = min(rl / g - (32 * wave) / g, 31);
+    const int n_slots = (32 * wave + 31) / g - (32 * wave) / g + 1;
+    const int t_first = tile * tpt;
+    const int t_last = min(t_first + tpt, T) - 1;
+    // One batch of loads, nothing waited for in between: this row's chunk start, the position id (or chunk start) of
+    // the lane's token slot, the chunk start of the tile's token `lane` (tokens 64 and up of a tile, which only small
+    // GQA groups have, follow below), then theta and the raw query rows.  Indices are clamped instead of branched on.
+    const int ts_lane = min(wave_t0 + (lane & (ROT_SLOTS - 1)), T - 1);
+    const int start_row_raw = a.tok_start[min(t, T - 1)];
+    const int slot_raw = a.pos ? a.pos[ts_lane] : a.tok_start[ts_lane];
+    const int start_tile_raw = a.tok_start[min(t_first + lane, t_last)];
+    __builtin_amdgcn_sched_barrier(0);
+    QLoads<D> ql;
+    issue_q_loads<D, true>((const __bf16*)a.q, a.theta_rev, rc, ql);
+
+    rc.key_lo = rc.valid ? min(max(start_row_raw, 0), t) : 0;
+    // position id of each token slot of this wave: given, or chunk-local
     auto pos_of_slot = [&](int s) {
         const int ts = min(wave_t0 + s, T - 1);
         return a.pos ? a.pos[ts] : ts - chunk_start(a.tok_start, ts);
     };
-    const int pos_lane = pos_of_slot(lane & (ROT_SLOTS - 1));
-    const int slot = min(rl / g - (32 * wave) / g, 31);
-    const int n_slots = (32 * wave + 31) / g - (32 * wave) / g + 1;
+    const int pos_lane = a.pos ? slot_raw : ts_lane - min(max(slot_raw, 0), ts_lane);
 
     // first row any token of the tile attends, and the largest such start (tiles below it need the lower mask);
     // the starts need not be monotone: a query token behind the documents starts at row 0 again
-    const int t_first = tile * tpt;
-    const int t_last = min(t_first + tpt, T) - 1;
     int lo_first = INT32_MAX, lo_last = 0;
-    for (int tt = t_first + lane; tt <= t_last; tt += 64) {
+    if (t_first + lane <= t_last) lo_first = lo_last = min(max(start_tile_raw, 0), t_first + lane);
+    for (int tt = t_first + 64 + lane; tt <= t_last; tt += 64) {
         const int st = chunk_start(a.tok_start, tt);
         lo_first = min(lo_first, st);
         lo_last = max(lo_last, st);
@@ -1103,8 +1135,7 @@ __global__ __launch_bounds__(64 * NW, 2) void blockdiag_attn_kernel(const TrBloc
     const Walk w = make_walk(kb, ke, T - 1, a.n_kv_heads, kvh, D);
 
     bf16x8 qf[D / 16];
-    prologue<D, NW, NS, HALF>((const __bf16*)a.q, (const __bf16*)a.k, (const __bf16*)a.v, w, rc, pos_lane, slot, n_slots, pos_of_slot,
-                        a.theta_rev, a.scale_log2e, smem, qf);
+    prologue<D, NW, NS, HALF>((const __bf16*)a.k, (const __bf16*)a.v, w, ql, pos_lane, slot, n_slots, pos_of_slot, a.scale_log2e, smem, qf);
 
     Acc<D> acc;
 #pragma unroll
