@@ -667,6 +667,37 @@ def test_linear_against_fp64_matmul(B, case):
     print("linear %s: max abs err %.3e, slices of k: %d" % ((M, feats, K), worst, B.tr_linear_workspace_size(M, feats, K) // max(1, M * sum(feats) * 4)))
 
 
+def _check_linear(B, M, feats, K, seed):
+    rng = np.random.Generator(np.random.PCG64([500, seed]))
+    x = synth.normal_tensor(rng, (M, K), torch.bfloat16)
+    ws_host = [(synth.normal_tensor(rng, (n, K), torch.float32) * K ** -0.5).to(torch.bfloat16) for n in feats]
+    ys = [torch.full((M, n), float("nan"), dtype=torch.bfloat16, device="cuda") for n in feats]
+    scratch = B.workspace(B.tr_linear_workspace_size(M, feats, K))
+    B.tr_linear(x.cuda(), [w.cuda() for w in ws_host], ys, scratch)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for w, y in zip(ws_host, ys):
+        want = oracle.linear(H.bits(x), H.bits(w))
+        got = H.to_f64(y)
+        assert np.isfinite(got).all()
+        err = np.abs(got - want)
+        assert (err <= 2.0 ** -8 * np.abs(want) + 1e-3).all(), "max abs err %.3e" % err.max()
+        worst = max(worst, float(err.max()))
+    return worst
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_linear_shapes(B, seed):
+    """Seeded random projection shapes: 1..128 rows (all four row-block counts and the two-workgroup split above 96
+    rows), one to four outputs of 32..1024 features, k a multiple of 16 up to 4096 (whole chunks, short last chunks,
+    a single k-step)."""
+    rng = np.random.Generator(np.random.PCG64([778, seed]))
+    M = int(rng.choice([1, 7, 31, 32, 33, 64, 65, 95, 96, 97, 127, 128])) if seed < 6 else int(rng.integers(1, 129))
+    feats = tuple(int(32 * rng.integers(1, 33)) for _ in range(int(rng.integers(1, 5))))
+    K = int(16 * rng.integers(1, 257))
+    print("random linear %d: M %d features %s K %d: max abs err %.3e" % (seed, M, feats, K, _check_linear(B, M, feats, K, 900 + seed)))
+
+
 # ---- seeded random shapes: group sizes, head dims, layouts, ragged lengths, all four attention entry points -------------
 def _random_case(seed):
     rng = np.random.Generator(np.random.PCG64([777, seed]))
