@@ -245,6 +245,7 @@ def main():
         roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
         roof_extra += bench_sequence(torch, B, synth, acct, mfma_roof)
         roof_extra += bench_decode(torch, B, synth, hbm_roof)
+        roof_extra += bench_short_query(torch, B, synth, hbm_roof)
         if args.host_store:
             roof_extra += bench_host_store(torch, B, synth, acct)
         result["layer_context"], lin_roofs = bench_layer_context(torch, B, synth, hbm_roof)
@@ -575,6 +576,34 @@ def bench_layer_context(torch, B, synth, hbm_roof):
     return {"what": "attention block of one layer: q/k/v projection (tr_linear, one launch for the three weights, random weights) + "
                     "step + output projection (tr_linear); the same block with torch.matmul for the projections beside it",
             "rows": rows}, roofs
+
+
+def bench_short_query(torch, B, synth, hbm_roof):
+    """A few query tokens over a long context (the shape of the paper's Table 2 workloads: 7.5k-16k context tokens,
+    6-20 query tokens): 16 query tokens over 12288 document rows, Qwen2-7B heads.  Every key is read once, so the row
+    is priced against HBM; twelve caches are cycled so that the keys do not sit in the last-level cache."""
+    sh = synth.QWEN2_7B
+    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20241012)
+    rnd = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    n_q, n_doc = 16, 12288
+    kv_len = n_doc + n_q
+    caches = [(rnd(kv_len, sh.n_kv_heads, sh.head_dim), rnd(kv_len, sh.n_kv_heads, sh.head_dim)) for _ in range(12)]
+    q = rnd(n_q, sh.n_q_heads, sh.head_dim)
+    out = torch.empty_like(q)
+    q_pos = torch.arange(n_doc, kv_len, dtype=torch.int32, device="cuda")
+    ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, n_q, kv_len))
+    c = {"i": 0}
+
+    def att():
+        c["i"] += 1
+        ck, cv = caches[c["i"] % len(caches)]
+        B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
+
+    t = _time_calls(torch, att, 24)
+    nbytes = 2 * kv_len * sh.n_kv_heads * sh.head_dim * 2 + 2 * n_q * sh.n_q_heads * sh.head_dim * 2
+    return [hbm_roof("tr_prefill_attn", "short-query-16-tokens-over-12288-rows-qwen2-7b", nbytes, t)]
 
 
 def bench_table4_batches(torch, B, synth):
