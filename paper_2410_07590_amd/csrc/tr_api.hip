@@ -441,7 +441,10 @@ struct ReqGeom { int32_t q_row0, n_q; int64_t kv_row0, kv_len; };
 constexpr int KEY_TILE = 64;
 constexpr int TARGET_ITEMS = 256;   // workgroups to aim for when splitting keys: one per CU (more splits cost more partial traffic than they gain)
 constexpr int MIN_SPLIT_KEYS = 256;
-constexpr int MAX_SPLIT = 32;       // the combine kernel holds one split per lane of a half-wave
+#ifndef TR_MAX_SPLIT
+#define TR_MAX_SPLIT 64
+#endif
+constexpr int MAX_SPLIT = TR_MAX_SPLIT;  // the combine kernel holds two splits per lane of a half-wave
 
 int env_int(const char* name, int dflt)
 {
@@ -936,7 +939,7 @@ int64_t plan_blockdiag(const tr_shape* sh, const int32_t* start_host, int64_t T,
         if (piece < 1) piece = 1;
         for (int64_t tile = 0; tile < n_tiles; ++tile) {
             const int st = (span[(size_t)tile] + KEY_TILE - 1) / KEY_TILE;
-            if (st > 2 * piece) ns[(size_t)tile] = std::min(MAX_SPLIT, (st + piece - 1) / piece);
+            if (st > 2 * piece) ns[(size_t)tile] = std::min(32, (st + piece - 1) / piece);
         }
         // runs of equal split count, at most TR_MAX_BD_SEG of them: else one run from the first to the last split tile
         int runs = 1;

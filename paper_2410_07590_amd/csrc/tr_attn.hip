@@ -978,7 +978,9 @@ __global__ __launch_bounds__(64 * SHORT_NW, 1) void short_attn_kernel(const TrPr
 // Merge the split-KV partial results: out = sum_s w_s l_s P_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s) and
 // P_s = O_s / l_s the normalised partial of split s.
 // 32 lanes per output row (4 channels each); lane i of the row also owns split i's statistics.
-template <int D>
+// WIDE: some request of the launch has more than 32 key splits, so a lane of the row's half-wave holds two of them
+// (splits i and i + 32); the narrow form keeps one and is what every launch with at most 32 splits runs.
+template <int D, bool WIDE>
 __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int total_rows)
 {
     static_assert(D == 128 || D == 64, "");
@@ -1001,18 +1003,23 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
     const int64_t rows_s = (int64_t)sd.n_q * g;
     const int64_t prow0 = (int64_t)sd.ws_row0 + kvh * rows_s + (tq - sd.q_row0) * g + hq % g;
     const int64_t pstride = (int64_t)a.n_kv_heads * rows_s; // partial rows between consecutive splits
-    // statistics: lane i < n_split (n_split <= 32) loads split i
-    float m_i = -INFINITY, l_i = 0.0f;
-    if (lane_r < sd.n_split) {
-        const float2 ml = *(const float2*)(a.ws_ml + (prow0 + lane_r * pstride) * 2);
-        m_i = ml.x;
-        l_i = ml.y;
-    }
-    float M = m_i;
+    // statistics: lane i of the row's half-wave loads split i (and split i + 32 in the wide form)
+    constexpr int NK = WIDE ? 2 : 1;
+    float m_i[2] = {-INFINITY, -INFINITY}, l_i[2] = {0.0f, 0.0f};
+#pragma unroll
+    for (int k = 0; k < NK; ++k)
+        if (lane_r + 32 * k < sd.n_split) {
+            const float2 ml = *(const float2*)(a.ws_ml + (prow0 + (lane_r + 32 * k) * pstride) * 2);
+            m_i[k] = ml.x;
+            l_i[k] = ml.y;
+        }
+    float M = fmaxf(m_i[0], m_i[1]);
 #pragma unroll
     for (int o = 16; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-    const float w_i = (m_i == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_i - M) * l_i;
-    float L = w_i;
+    float w_i[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) w_i[k] = (k >= NK || m_i[k] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_i[k] - M) * l_i[k];
+    float L = w_i[0] + w_i[1];
 #pragma unroll
     for (int o = 16; o >= 1; o >>= 1) L += __shfl_xor(L, o);
     float acc[CPLN];
@@ -1025,6 +1032,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
     for (int sp0 = 0; sp0 < sd.n_split; sp0 += PER_ROUND) {
         f32x4 x[PER_ROUND];
         float w[PER_ROUND];
+        const float w_src = (!WIDE || sp0 < 32) ? w_i[0] : w_i[1]; // a round never straddles 32
 #pragma unroll
         for (int u = 0; u < PER_ROUND; ++u) {
             const int sp = sp0 + u;
@@ -1038,7 +1046,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const TrPrefixArgs a, int 
                 const f16x2 t = *(const f16x2*)p;
                 x[u][0] = (float)t[0]; x[u][1] = (float)t[1]; x[u][2] = 0.0f; x[u][3] = 0.0f;
             }
-            const float ws = __shfl(w_i, row_lane0 + (ok ? sp : 0));
+            const float ws = __shfl(w_src, row_lane0 + (sp & 31));
             w[u] = ok ? ws : 0.0f;
         }
 #pragma unroll
@@ -1244,6 +1252,22 @@ int blockdiag_dispatch(const TrBlockDiagArgs& a, int head_dim, int wg_rows, hipS
 
 } // namespace
 
+// the merge kernel for a launch whose largest split count is max_split
+static int launch_combine(const TrPrefixArgs& a, int head_dim, int blocks, int total_rows, hipStream_t s)
+{
+    int max_split = 1;
+    for (int i = 0; i < a.n_seq; ++i) max_split = a.seq[i].n_split > max_split ? a.seq[i].n_split : max_split;
+    if (max_split > 32) {
+        if (head_dim == 128) hipLaunchKernelGGL((combine_kernel<128, true>), dim3(blocks), dim3(256), 0, s, a, total_rows);
+        else hipLaunchKernelGGL((combine_kernel<64, true>), dim3(blocks), dim3(256), 0, s, a, total_rows);
+    } else {
+        if (head_dim == 128) hipLaunchKernelGGL((combine_kernel<128, false>), dim3(blocks), dim3(256), 0, s, a, total_rows);
+        else hipLaunchKernelGGL((combine_kernel<64, false>), dim3(blocks), dim3(256), 0, s, a, total_rows);
+    }
+    TR_HIP(hipGetLastError());
+    return TR_OK;
+}
+
 // wg_rows: 128 (4 waves, 2-stage ring, two workgroups per CU), 256 (8 waves, 4-stage ring, one per CU) or 32 (the
 // short-query kernel: 4 waves share 32 rows and split the keys)
 int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool any_split, int total_rows, hipStream_t s)
@@ -1254,9 +1278,7 @@ int tr_launch_prefix_attn(const TrPrefixArgs& a, int head_dim, int wg_rows, bool
     if (any_split) {
         const int rows_per_block = 256 / 32;
         const int blocks = (total_rows + rows_per_block - 1) / rows_per_block;
-        if (head_dim == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3(blocks), dim3(256), 0, s, a, total_rows);
-        else hipLaunchKernelGGL(combine_kernel<64>, dim3(blocks), dim3(256), 0, s, a, total_rows);
-        TR_HIP(hipGetLastError());
+        if (int rc2 = launch_combine(a, head_dim, blocks, total_rows, s)) return rc2;
     }
     return TR_OK;
 }
@@ -1271,9 +1293,7 @@ int tr_launch_gather_attn(const TrGatherArgs& a, const TrPrefixArgs& combine_arg
     if (a.n_split > 1) {
         const int total_rows = a.n_q * a.n_q_heads;
         const int blocks = (total_rows + 7) / 8;
-        if (head_dim == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3(blocks), dim3(256), 0, s, combine_args, total_rows);
-        else hipLaunchKernelGGL(combine_kernel<64>, dim3(blocks), dim3(256), 0, s, combine_args, total_rows);
-        TR_HIP(hipGetLastError());
+        if (int rc2 = launch_combine(combine_args, head_dim, blocks, total_rows, s)) return rc2;
     }
     return TR_OK;
 }
@@ -1286,9 +1306,7 @@ int tr_launch_blockdiag_attn(const TrBlockDiagArgs& a, const TrPrefixArgs* combi
     if (rc) return rc;
     if (combine && combine_rows > 0) {
         const int blocks = (combine_rows + 7) / 8;
-        if (head_dim == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3(blocks), dim3(256), 0, s, *combine, combine_rows);
-        else hipLaunchKernelGGL(combine_kernel<64>, dim3(blocks), dim3(256), 0, s, *combine, combine_rows);
-        TR_HIP(hipGetLastError());
+        if (int rc2 = launch_combine(*combine, head_dim, blocks, combine_rows, s)) return rc2;
     }
     return TR_OK;
 }

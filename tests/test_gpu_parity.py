@@ -311,6 +311,25 @@ def test_decode_split_keys(B):
     print("decode split: max abs err %.3e" % _check_batched(B, cfg, store, sd, reqs, decode=True))
 
 
+def test_more_than_32_key_splits(B):
+    """One request with a long context and few query rows: fewer workgroups than CUs unless the keys are cut into more
+    than 32 pieces, which the merge kernel then handles two per lane.  16 query tokens (one row tile of the 128-row
+    kernel, streaming tile loads) and one query token (the short-query kernel) over 26 chunks of 450..550 rows."""
+    for n_q in (16, 1):
+        cfg = synth.scaled(synth.CONFIGS[2], store_chunks=30, chunk_len_lo=450, chunk_len_hi=550, n_requests=1,
+                           chunks_per_request=26, n_q_lo=n_q, n_q_hi=n_q)
+        store = synth.make_store(cfg)
+        sd = _store_dev(B, cfg.shape, store)
+        req = synth.make_requests(cfg, store)[0]
+        gs = H.gpu_shape(B, cfg.shape)
+        kv_len = req.n_doc + req.n_q
+        per_split_rows = req.n_q * cfg.shape.n_q_heads * (cfg.shape.head_dim * 2 + 8)
+        n_split = B.tr_prefill_attn_workspace_size(gs, req.n_q, kv_len) // per_split_rows
+        assert n_split > 32, "this case is meant to use more than 32 splits, the plan has %d" % n_split
+        err, n_bad = H.check_request(B, cfg.shape, store, sd, req)
+        print("%d query tokens over %d rows, about %d splits: max abs err %.3e" % (req.n_q, kv_len, n_split, err))
+
+
 def test_decode_full_batch64_kv4k(B):
     """64 requests x 8 chunks of 512 rows at the Qwen2-7B shape: the size the decode bench line is quoted on."""
     cfg = synth.scaled(synth.CONFIGS[2], n_requests=64, n_q_lo=1, n_q_hi=1)
