@@ -515,8 +515,18 @@ def bench_layer_context(torch, B, synth, hbm_roof):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20241013)
     rnd = lambda *shape, scale=1.0: (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * scale).to(torch.bfloat16)
-    wq, wo = rnd(hidden, hidden, scale=hidden ** -0.5), rnd(hidden, hidden, scale=hidden ** -0.5)   # [out_features, in_features]
-    wk, wv = (rnd(sh.n_kv_heads * sh.head_dim, hidden, scale=hidden ** -0.5) for _ in range(2))
+    # the weights of N_LAYERS layers are used in turn, as a model walks through them: 587 MB (257 MB of output
+    # weights alone), more than the 256 MB last-level cache holds, so that no call finds its weights cached
+    N_LAYERS = 10
+    layers = [(rnd(hidden, hidden, scale=hidden ** -0.5), rnd(sh.n_kv_heads * sh.head_dim, hidden, scale=hidden ** -0.5),
+               rnd(sh.n_kv_heads * sh.head_dim, hidden, scale=hidden ** -0.5), rnd(hidden, hidden, scale=hidden ** -0.5))
+              for _ in range(N_LAYERS)]    # (wq, wk, wv, wo), each [out_features, in_features]
+    wq, wk, wv, wo = layers[0]
+    turn = {"i": 0}
+
+    def next_layer():
+        turn["i"] += 1
+        return layers[turn["i"] % N_LAYERS]
     rows, roofs = [], []
     for name, n_chunks, n_q in (("qwen2-7b-8x512-q64", 8, 64), ("table4-shape-16x512-q128", 16, 128)):
         n_store = 64
@@ -540,6 +550,7 @@ def bench_layer_context(torch, B, synth, hbm_roof):
             B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, att, ws)
 
         def layer_library():
+            wq, wk, wv, wo = next_layer()
             torch.matmul(x, wq.t(), out=q.view(n_q, hidden))
             torch.matmul(x, wk.t(), out=kq.view(n_q, -1))
             torch.matmul(x, wv.t(), out=vq.view(n_q, -1))
@@ -550,22 +561,31 @@ def bench_layer_context(torch, B, synth, hbm_roof):
         ws_o = B.workspace(B.tr_linear_workspace_size(n_q, [hidden], hidden))
 
         def layer():
+            wq, wk, wv, wo = next_layer()
             B.tr_linear(x, [wq, wk, wv], [q, kq, vq], ws_qkv)
             step()
             B.tr_linear(att.view(n_q, hidden), wo, o, ws_o)
 
         def projections():
+            wq, wk, wv, wo = next_layer()
             B.tr_linear(x, [wq, wk, wv], [q, kq, vq], ws_qkv)
             B.tr_linear(att.view(n_q, hidden), wo, o, ws_o)
 
-        t_layer = _time_calls(torch, layer, 20)
-        t_lib = _time_calls(torch, layer_library, 20)
+        def proj_qkv():
+            wq, wk, wv, _ = next_layer()
+            B.tr_linear(x, [wq, wk, wv], [q, kq, vq], ws_qkv)
+
+        def proj_o():
+            B.tr_linear(att.view(n_q, hidden), next_layer()[3], o, ws_o)
+
+        t_layer = _time_calls(torch, layer, 24)
+        t_lib = _time_calls(torch, layer_library, 24)
         t_step = _time_calls(torch, step, 20)
-        t_proj = _time_calls(torch, projections, 20)
+        t_proj = _time_calls(torch, projections, 24)
         if n_q == 64:   # roofline rows for the two launches: weights, x and y moved once
             n_qkv = wq.shape[0] + wk.shape[0] + wv.shape[0]
-            t_qkv = _time_calls(torch, lambda: B.tr_linear(x, [wq, wk, wv], [q, kq, vq], ws_qkv), 20)
-            t_o = _time_calls(torch, lambda: B.tr_linear(att.view(n_q, hidden), wo, o, ws_o), 20)
+            t_qkv = _time_calls(torch, proj_qkv, 24)
+            t_o = _time_calls(torch, proj_o, 24)
             roofs.append(hbm_roof("tr_linear", "qwen2-7b-qkv-projection-64-tokens", 2 * (n_qkv * hidden + n_q * hidden + n_q * n_qkv), t_qkv))
             roofs.append(hbm_roof("tr_linear", "qwen2-7b-output-projection-64-tokens", 2 * (hidden * hidden + 2 * n_q * hidden), t_o))
         w_bytes = 2 * (wq.numel() + wk.numel() + wv.numel() + wo.numel())
@@ -574,7 +594,8 @@ def bench_layer_context(torch, B, synth, hbm_roof):
                      "weight_stream_gbs": round(w_bytes / (t_proj[0] * 1e-6) / 1e9, 1),
                      "attention_block_with_library_gemms_us": round(t_lib[0], 2)})
     return {"what": "attention block of one layer: q/k/v projection (tr_linear, one launch for the three weights, random weights) + "
-                    "step + output projection (tr_linear); the same block with torch.matmul for the projections beside it",
+                    "step + output projection (tr_linear); the same block with torch.matmul for the projections beside it; "
+                    "the weights of %d layers are used in turn (%d MB, more than the last-level cache holds)" % (N_LAYERS, N_LAYERS * 58720256 // 1000000),
             "rows": rows}, roofs
 
 
