@@ -424,3 +424,35 @@ def test_linear_validation(L):
     assert L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), big_p, C.c_int32(3584)) == 0   # enough row tiles: no slicing
     bad, bad_p = _i32([3600])
     assert L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), bad_p, C.c_int32(3584)) == 0   # invalid shape: 0
+
+
+def test_launch_planners_on_random_request_mixes(L):
+    """The host-side launch planners (key splits per request, chosen by playing the launch through) on 300 seeded
+    random request mixes, through the workspace-size entry points: they return, the same input gives the same size,
+    and the size stays within what the largest allowed number of key splits could need (64 partial rows of head_dim
+    fp16 values plus two fp32 statistics per query row and head)."""
+    rng = np.random.Generator(np.random.PCG64(4242))
+    for case in range(300):
+        hkv = int(rng.choice([1, 2, 4, 8]))
+        g = int(rng.choice([1, 2, 4, 7, 8]))
+        d = int(rng.choice([64, 128]))
+        sh = B.make_shape(hkv * g, hkv, d, "bf16", 1.0e6)
+        n_req = int(rng.integers(1, 24))
+        n_q = rng.integers(0, 200, n_req) if case % 3 else rng.integers(0, 20, n_req)
+        n_doc = rng.integers(0, 40000, n_req) if case % 2 else rng.integers(0, 3000, n_req)
+        cu_q = np.concatenate([[0], np.cumsum(n_q)]).astype(np.int32)
+        crs = np.concatenate([[0], np.cumsum(n_doc + n_q)]).astype(np.int64)
+        size = B.tr_prefill_attn_batched_workspace_size(sh, cu_q, crs)
+        assert size == B.tr_prefill_attn_batched_workspace_size(sh, cu_q, crs)
+        bound = 64 * int(n_q.sum()) * hkv * g * (2 * d + 8) + 256
+        assert 0 <= size <= bound, (case, size, bound)
+        one = B.tr_prefill_attn_workspace_size(sh, int(n_q[0]), int(n_doc[0] + n_q[0]))
+        assert 0 <= one <= 64 * int(n_q[0]) * hkv * g * (2 * d + 8) + 256
+        dec = B.tr_decode_attn_workspace_size(sh, np.concatenate([[0], np.cumsum(n_doc + 1)]).astype(np.int64))
+        assert 0 <= dec <= 64 * n_req * hkv * g * (2 * d + 8) + 256
+        # a packed sequence: the documents of the first request as chunks, its query tokens as the tail
+        lens = [int(x) for x in rng.integers(0, 1500, int(rng.integers(0, 12)))]
+        seg, pos = B.tr_sequence_plan(lens, int(n_q[0]), int(case % 2))
+        if seg.size:
+            ws = B.tr_sequence_prefill_attn_workspace_size(sh, seg, seg.size)
+            assert 0 <= ws <= 64 * seg.size * hkv * g * (2 * d + 8) + 256
