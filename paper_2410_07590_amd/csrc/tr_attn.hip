@@ -296,8 +296,11 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* krows, const b
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32)); // both half-waves hold keys of the same query column
     // lazy reference update (exact: any reference gives the same softmax).  `first`: nothing accumulated yet and the
-    // tile sits far below the reference - move the reference down so that exp2 does not underflow.
-    const bool first = (acc.l == 0.0f) && (mx < REREF_BELOW) && (mx > -INFINITY);
+    // tile sits far below the reference - move the reference down so that exp2 does not underflow.  Lanes c and c + 32
+    // hold the two key halves of ONE query column and share its reference, so the decision is taken on the column's
+    // denominator: a row whose first visible keys all fell into one half must not move the other half's reference alone.
+    const float l_col = acc.l + __shfl_xor(acc.l, 32);
+    const bool first = (l_col == 0.0f) && (mx < REREF_BELOW) && (mx > -INFINITY);
     const bool grow = (mx > RESCALE_SLACK) || first;
     if (__any(grow)) { // rare
         const float delta = grow ? mx : 0.0f;
