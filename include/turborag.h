@@ -25,7 +25,8 @@
  *   - Every function returns a tr_status (0 = TR_OK, negative = error).  tr_last_error() returns a
  *     thread-local message for the last error on the calling thread.  Nothing throws, aborts or prints.
  *   - Results are deterministic: same inputs, same bits (no atomics in any reduction).  How a launch is cut into
- *     workgroups depends only on the shapes and lengths passed in (and, for tuning, on TR_* environment variables).
+ *     workgroups depends only on the shapes and lengths passed in; the library reads no environment variable
+ *     (tr_set_tuning is the one, explicit, way to override the launch policy).
  *   - RoPE follows Eq. 3: pair m of a head is turned by pos * theta_m, theta_m = rope_base^(-2m/head_dim).
  *     TR_ROPE_INTERLEAVED: pair m = channels (2m, 2m+1), the layout Eq. 3 prints.  TR_ROPE_HALF: pair m =
  *     channels (m, m + head_dim/2), the layout in which the released weights of the models of Sec. 4 keep
@@ -258,6 +259,14 @@ int tr_sequence_prefill_attn(const tr_shape* shape, const void* q, const void* k
 size_t tr_linear_workspace_size(int32_t M, int32_t n_out, const int32_t* n_features /*host*/, int32_t K);
 int tr_linear(const void* x, int32_t M, int32_t K, int32_t n_out, const void* const* w /*host*/, void* const* y /*host*/,
               const int32_t* n_features /*host*/, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- launch-policy override for tests and sweeps -------------------------------------------------------------------------
+ * Sets a process-wide override of one value of the launch policy; value 0 restores the default.  Names: "wg_rows"
+ * (packed rows per attention workgroup: 32, 128, 256), "target_items", "min_split_keys", "asm_span", "bd_piece_tiles",
+ * "bd_slots", "lin_split", "lin_msplit".  Results never depend on these beyond the rounding of a different
+ * summation order; a *_workspace_size() query and the call it sizes must see the same overrides.  Not meant for
+ * concurrent use with running calls.  Errors: TR_ERR_INVALID_ARG (unknown name, negative value). */
+int tr_set_tuning(const char* name, int32_t value);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,7 @@ EXPORTS = [
     "tr_decode_attn_workspace_size", "tr_decode_attn",
     "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
     "tr_sequence_plan", "tr_sequence_prefill_attn_workspace_size", "tr_sequence_prefill_attn",
-    "tr_linear_workspace_size", "tr_linear",
+    "tr_linear_workspace_size", "tr_linear", "tr_set_tuning",
 ]
 
 
@@ -204,6 +204,10 @@ def tr_prefill_attn(shape, q, k, v, q_pos, kv_len, out, workspace=None, stream=N
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().tr_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), C.c_int32(q.shape[0]),
                                  C.c_int64(kv_len), _dev(out), _dev(workspace), C.c_size_t(ws_bytes), _stream(stream)))
+
+
+def tr_set_tuning(name, value):
+    _check(lib().tr_set_tuning(name.encode(), C.c_int32(int(value))))
 
 
 def tr_prefill_attn_batched_workspace_size(shape, cu_q, cache_row_start):

@@ -25,6 +25,30 @@ void tr_clear_error() { g_err[0] = 0; }
 
 extern "C" const char* tr_last_error(void) { return g_err; }
 
+// ---- launch-policy overrides ----------------------------------------------------------------------------------------
+static std::atomic<int> g_knob[TR_KNOB_COUNT];
+static const char* const KNOB_NAMES[TR_KNOB_COUNT] = {"wg_rows", "target_items", "min_split_keys", "asm_span",
+                                                      "bd_piece_tiles", "bd_slots", "lin_split", "lin_msplit"};
+
+int tr_knob(int which, int dflt)
+{
+    const int v = g_knob[which].load(std::memory_order_relaxed);
+    return v != 0 ? v : dflt;
+}
+
+extern "C" int tr_set_tuning(const char* name, int32_t value)
+{
+    tr_clear_error();
+    if (!name) return tr_fail(TR_ERR_INVALID_ARG, "tr_set_tuning: name is NULL");
+    if (value < 0) return tr_fail(TR_ERR_INVALID_ARG, "tr_set_tuning: value %d is negative", value);
+    for (int i = 0; i < TR_KNOB_COUNT; ++i)
+        if (strcmp(name, KNOB_NAMES[i]) == 0) {
+            g_knob[i].store(value, std::memory_order_relaxed);
+            return TR_OK;
+        }
+    return tr_fail(TR_ERR_INVALID_ARG, "tr_set_tuning: unknown name '%s'", name);
+}
+
 // No C++ exception may cross the C boundary: the entry points run inside these.
 template <class F> static int tr_guard_int(F&& f)
 {
@@ -154,7 +178,7 @@ int launch_runs(const tr_store* store, const std::vector<CopyRun>& runs, void* o
     span = ((span + 255) / 256) * 256;
     if (span < 256) span = 256;
     if (span > 4096) span = 4096;
-    if (const char* e = getenv("TR_ASM_SPAN")) { if (atoi(e) >= 256) span = (atoi(e) / 256) * 256; } // tuning aid
+    if (const int forced = tr_knob(TR_KNOB_ASM_SPAN, 0); forced >= 256) span = (forced / 256) * 256;
 
     TrAssembleArgs a;
     memset(&a, 0, sizeof a);
@@ -439,24 +463,18 @@ namespace {
 struct ReqGeom { int32_t q_row0, n_q; int64_t kv_row0, kv_len; };
 
 constexpr int KEY_TILE = 64;
-constexpr int TARGET_ITEMS = 256;   // workgroups to aim for when splitting keys: one per CU (more splits cost more partial traffic than they gain)
+constexpr int TARGET_ITEMS = TrChip::CUS;   // workgroups to aim for when splitting keys: one per CU (more splits cost more partial traffic than they gain)
 constexpr int MIN_SPLIT_KEYS = 256;
 #ifndef TR_MAX_SPLIT
 #define TR_MAX_SPLIT 64
 #endif
 constexpr int MAX_SPLIT = TR_MAX_SPLIT;  // the combine kernel holds two splits per lane of a half-wave
 
-int env_int(const char* name, int dflt)
-{
-    const char* e = getenv(name);
-    return (e && *e) ? atoi(e) : dflt;
-}
-
 // Packed rows per workgroup: 256 (8 waves, deep LDS ring) when one KV head has enough rows to fill such tiles,
-// else 128 (4 waves).  TR_WG_ROWS overrides (tuning aid).
+// else 128 (4 waves).  The wg_rows override of tr_set_tuning wins.
 int pick_wg_rows(const tr_shape* sh, int64_t max_rows_per_kv_head)
 {
-    const int forced = env_int("TR_WG_ROWS", 0);
+    const int forced = tr_knob(TR_KNOB_WG_ROWS, 0);
     const int g = sh->n_q_heads / sh->n_kv_heads;
     if (forced == 128 || forced == 256 || (forced == 32 && g <= 32)) return forced;
     if (max_rows_per_kv_head <= 32) return 32; // decode and other very short queries: waves split keys, not rows
@@ -480,15 +498,16 @@ SplitPlan cut_keys(int64_t kv_len, int want, int min_split_keys, int key_tile)
 }
 
 // Finishing time, in key-tile steps, of a launch whose items (in launch order) walk item_tiles[i] key tiles each.
-// Blocks are dealt round-robin to the 8 XCDs and the kernels map each XCD to one contiguous range of items, so
+// Blocks are dealt round-robin to the XCDs and the kernels map each XCD to one contiguous range of items, so
 // every XCD works through its own range on its own slots; a workgroup costs FIXED steps besides its tiles.
 double launch_makespan(const std::vector<int>& item_tiles, int slots_per_xcd)
 {
-    const double FIXED = 3.0;
-    const size_t n = item_tiles.size(), q = n / 8, r = n % 8;
+    const double FIXED = TrChip::WORKGROUP_FIXED_STEPS;
+    const size_t X = TrChip::XCDS;
+    const size_t n = item_tiles.size(), q = n / X, r = n % X;
     double worst = 0.0;
     std::vector<double> slot;
-    for (size_t x = 0; x < 8; ++x) {
+    for (size_t x = 0; x < X; ++x) {
         const size_t lo = x * q + std::min(x, r), hi = lo + q + (x < r ? 1 : 0);
         slot.assign((size_t)slots_per_xcd, 0.0);
         for (size_t i = lo; i < hi; ++i) { // the next block goes to the slot that frees first
@@ -510,8 +529,8 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
     for (size_t r = r0; r < r1; ++r) max_rows = std::max<int64_t>(max_rows, (int64_t)reqs[r].n_q * g);
     const int wg_rows = pick_wg_rows(sh, max_rows);
     const int tpt = wg_rows / g;
-    const int target = env_int("TR_TARGET_ITEMS", TARGET_ITEMS);
-    const int min_split_keys = std::max(KEY_TILE, env_int("TR_MIN_SPLIT_KEYS", MIN_SPLIT_KEYS));
+    const int target = tr_knob(TR_KNOB_TARGET_ITEMS, TARGET_ITEMS);
+    const int min_split_keys = std::max(KEY_TILE, tr_knob(TR_KNOB_MIN_SPLIT_KEYS, MIN_SPLIT_KEYS));
     int64_t base_items = 0;
     for (size_t r = r0; r < r1; ++r) base_items += (int64_t)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads;
     int want_split = 1;
@@ -524,16 +543,16 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
     // and how the launch then packs onto the chip swings by tens of percent with the count.  Instead every request is
     // cut into pieces of about one common length, and that length is chosen by playing the launch through
     // (launch_makespan) for a range of candidates, with the traffic of the partial results priced in.
-    if (want_split > 1 && r1 - r0 > 1 && wg_rows != 32 && !getenv("TR_TARGET_ITEMS")) {
+    if (want_split > 1 && r1 - r0 > 1 && wg_rows != 32 && tr_knob(TR_KNOB_TARGET_ITEMS, 0) == 0) {
         double walked = 0.0; // keys walked by all row tiles of all KV heads
         for (size_t r = r0; r < r1; ++r) walked += (double)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads * (double)reqs[r].kv_len;
-        const int slots_per_xcd = wg_rows == 256 ? 32 : 64;
-        const double STEP_US = 2.0, PARTIAL_BYTES_PER_US = 2.0e6; // a key-tile step; write + read of partials at ~4 TB/s
+        const int slots_per_xcd = (wg_rows == 256 ? TrChip::SLOTS_256 : TrChip::SLOTS_128) / TrChip::XCDS;
+        const double STEP_US = TrChip::KEY_TILE_STEP_US, PARTIAL_BYTES_PER_US = TrChip::PARTIAL_BYTES_PER_US;
         double best = 1e300;
         std::vector<SplitPlan> cand(r1 - r0);
         std::vector<int> item_tiles;
         for (int c = 0; c < 24; ++c) {
-            const double n_items = 8.0 * slots_per_xcd * 0.75 * pow(4.0 / 0.75, c / 23.0); // 0.75x .. 4x the resident workgroups
+            const double n_items = (double)TrChip::XCDS * slots_per_xcd * 0.75 * pow(4.0 / 0.75, c / 23.0); // 0.75x .. 4x the resident workgroups
             const double keys_per_item = walked / n_items;
             item_tiles.clear();
             double partial_bytes = 0.0;
@@ -908,7 +927,7 @@ extern "C" int tr_sequence_plan(const int32_t* chunk_lens, int32_t n_chunks, int
 
 namespace {
 
-constexpr int BD_SLOTS = 512;        // 128-row workgroups resident at once: two per CU
+constexpr int BD_SLOTS = TrChip::SLOTS_128; // 128-row workgroups resident at once: two per CU
 constexpr int BD_MIN_PIECE_TILES = 16;
 
 // Work list of the block-diagonal kernel.  Without a host copy of the starts every row tile is one item per KV head.
@@ -931,11 +950,11 @@ int64_t plan_blockdiag(const tr_shape* sh, const int32_t* start_host, int64_t T,
             span[(size_t)tile] = (int32_t)(t1 - lo);
             walked += (double)((t1 - lo + KEY_TILE - 1) / KEY_TILE);
         }
-        const int slots = std::max(1, env_int("TR_BD_SLOTS", BD_SLOTS));
+        const int slots = std::max(1, tr_knob(TR_KNOB_BD_SLOTS, BD_SLOTS));
         const double fair = walked * sh->n_kv_heads / slots; // key tiles per resident workgroup
         int piece = (int)(fair / 3.0);
         if (piece < BD_MIN_PIECE_TILES) piece = BD_MIN_PIECE_TILES;
-        piece = env_int("TR_BD_PIECE_TILES", piece);
+        piece = tr_knob(TR_KNOB_BD_PIECE_TILES, piece);
         if (piece < 1) piece = 1;
         for (int64_t tile = 0; tile < n_tiles; ++tile) {
             const int st = (span[(size_t)tile] + KEY_TILE - 1) / KEY_TILE;
@@ -1019,7 +1038,7 @@ size_t blockdiag_ws_bytes(const tr_shape* sh, int64_t ws_rows)
 
 int sequence_tok_per_tile(const tr_shape* sh, int* wg_rows)
 {
-    *wg_rows = env_int("TR_WG_ROWS", 0) == 256 ? 256 : 128;
+    *wg_rows = tr_knob(TR_KNOB_WG_ROWS, 0) == 256 ? 256 : 128;
     return *wg_rows / (sh->n_q_heads / sh->n_kv_heads);
 }
 
@@ -1244,7 +1263,7 @@ extern "C" int tr_chunk_prefill_attn(const tr_shape* shape, const void* q, const
     a.rope_half = tr_rope_half(shape);
     // chunks are short (a row tile walks a few key tiles only), so two independent 4-wave workgroups per CU, which
     // overlap one's prologue and epilogue with the other's tile loop, beat one 8-wave workgroup
-    const int forced_rows = env_int("TR_WG_ROWS", 0);
+    const int forced_rows = tr_knob(TR_KNOB_WG_ROWS, 0);
     const int wg_rows = forced_rows == 256 ? 256 : 128;
     a.tok_per_tile = wg_rows / a.group;
     a.n_tiles = (int32_t)((total_tokens + a.tok_per_tile - 1) / a.tok_per_tile);

@@ -233,16 +233,7 @@ __device__ __forceinline__ void append_pair(const void* k_new, const void* v_new
 // the (cos, sin) of "its" pairs for this chunk's offset are loop constants.
 constexpr int ASM_UNROLL = 4;
 
-__device__ __forceinline__ void st_stream(uint4* p, uint4 x)
-{
-#ifdef TR_ASM_NT_STORE
-    u32x4 r;
-    r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
-    __builtin_nontemporal_store(r, (u32x4*)p);
-#else
-    *p = x;
-#endif
-}
+__device__ __forceinline__ void st_stream(uint4* p, uint4 x) { *p = x; }
 
 template <int DTYPE, bool HALF>
 __global__ __launch_bounds__(256) void assemble_kernel(const TrAssembleArgs a)

@@ -43,6 +43,35 @@ struct tr_store {
     std::vector<int64_t> row_start; // n_chunks + 1
 };
 
+// ---- launch-policy overrides (tr_set_tuning) --------------------------------------------------------------------
+// The library reads no environment variable.  Tests and sweeps override a policy value through tr_set_tuning();
+// tr_knob() returns the override, or dflt when none is set (0 = not set).
+enum TrKnob {
+    TR_KNOB_WG_ROWS,        // packed rows per attention workgroup: 32, 128 or 256
+    TR_KNOB_TARGET_ITEMS,   // workgroups a single request's key split aims for
+    TR_KNOB_MIN_SPLIT_KEYS, // shortest key split
+    TR_KNOB_ASM_SPAN,       // 16-byte units of K (and V) per assemble workgroup
+    TR_KNOB_BD_PIECE_TILES, // key tiles per piece when the one-pass kernel cuts a long key range
+    TR_KNOB_BD_SLOTS,       // resident workgroups the one-pass planner balances for
+    TR_KNOB_LIN_SPLIT,      // slices of k in tr_linear
+    TR_KNOB_LIN_MSPLIT,     // 1: never split the rows of x over two workgroups
+    TR_KNOB_COUNT
+};
+int tr_knob(int which, int dflt);
+
+// ---- the chip the launch planners are written for (MI355X, gfx950) ------------------------------------------------
+// One table instead of constants scattered over the planners.  The *_US and *_PER_US figures are measured on that
+// part and only steer how work is cut; no result depends on them.
+struct TrChip {
+    static constexpr int XCDS = 8;                 // accelerator dies; blocks are dealt to them round-robin
+    static constexpr int CUS = 256;                // compute units, 32 per XCD
+    static constexpr int SLOTS_128 = 512;          // resident 128-row attention workgroups (two per CU)
+    static constexpr int SLOTS_256 = 256;          // resident 256-row attention workgroups (one per CU)
+    static constexpr double KEY_TILE_STEP_US = 2.0;        // one 64-key step of a resident attention workgroup
+    static constexpr double WORKGROUP_FIXED_STEPS = 3.0;   // prologue + epilogue of a workgroup, in such steps
+    static constexpr double PARTIAL_BYTES_PER_US = 2.0e6;  // split partials, written and read back: ~4 TB/s for both
+};
+
 // theta_m = base^(-2m/d) in double (text after Eq. 3)
 void tr_fill_theta(const tr_shape* s, double* theta /*[64]*/);
 

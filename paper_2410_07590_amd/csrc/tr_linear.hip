@@ -235,10 +235,10 @@ __global__ __launch_bounds__(256) void linear_combine_kernel(const TrLinearArgs 
 static bool lin_large(int32_t N, int32_t K) { return (int64_t)N * K * 2 >= LIN_LARGE_WEIGHT_BYTES; }
 // More than 96 rows of x against a small weight: two workgroups per item, one per 64 rows, each with the ring of
 // three chunks that 64 rows leave room for (128 rows x 4608 x 3584: 20.7 -> 18.9 us; at 65..96 rows and for large
-// weights one workgroup per item measured faster).  TR_LIN_MSPLIT=1 keeps one (tuning aid).
+// weights one workgroup per item measured faster).  tr_set_tuning("lin_msplit", 1) keeps one.
 static int lin_m_split(int32_t M, int32_t N, int32_t K)
 {
-    if (const char* e = getenv("TR_LIN_MSPLIT")) { if (atoi(e) == 1) return 1; }
+    if (tr_knob(TR_KNOB_LIN_MSPLIT, 0) == 1) return 1;
     return (M > 96 && !lin_large(N, K)) ? 2 : 1;
 }
 
@@ -248,7 +248,7 @@ int tr_linear_splits(int32_t M, int32_t N, int32_t K)
     int n_split = ((lin_large(N, K) ? 450 : 200) + groups / 2) / groups;
     if (n_split > chunks / 2) n_split = chunks / 2;
     if (n_split > LIN_MAX_SPLIT) n_split = LIN_MAX_SPLIT;
-    if (const char* e = getenv("TR_LIN_SPLIT")) { if (atoi(e) >= 1 && atoi(e) <= chunks && atoi(e) <= LIN_MAX_SPLIT) n_split = atoi(e); } // tuning aid
+    if (const int forced = tr_knob(TR_KNOB_LIN_SPLIT, 0); forced >= 1 && forced <= chunks && forced <= LIN_MAX_SPLIT) n_split = forced;
     if (n_split < 1) n_split = 1;
     return n_split;
 }

@@ -240,6 +240,21 @@ def test_prefill_attn_validation_and_workspace(L):
     assert call(n_q=0, kv_len=100) == B.TR_OK
 
 
+def test_set_tuning_validation_and_effect(L):
+    sh = _shape()
+    assert L.tr_set_tuning(None, C.c_int32(1)) == B.TR_ERR_INVALID_ARG
+    assert L.tr_set_tuning(b"no_such_knob", C.c_int32(1)) == B.TR_ERR_INVALID_ARG
+    assert b"no_such_knob" in L.tr_last_error()
+    assert L.tr_set_tuning(b"wg_rows", C.c_int32(-1)) == B.TR_ERR_INVALID_ARG
+    base = L.tr_prefill_attn_workspace_size(C.byref(sh), C.c_int32(64), C.c_int64(4160))
+    assert L.tr_set_tuning(b"target_items", C.c_int32(32)) == B.TR_OK
+    try:
+        assert L.tr_prefill_attn_workspace_size(C.byref(sh), C.c_int32(64), C.c_int64(4160)) < base   # fewer key splits
+    finally:
+        assert L.tr_set_tuning(b"target_items", C.c_int32(0)) == B.TR_OK
+    assert L.tr_prefill_attn_workspace_size(C.byref(sh), C.c_int32(64), C.c_int64(4160)) == base
+
+
 def test_prefill_attn_batched_validation(L):
     sh = _shape()
     cu, cu_p = _i32([0, 40, 100])

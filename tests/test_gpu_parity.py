@@ -367,9 +367,23 @@ def test_more_requests_than_one_launch_describes(B):
         print("70 requests (decode=%s): max abs err %.3e" % (decode, _check_batched(B, cfg, store, sd, reqs, decode=decode)))
 
 
-def test_short_query_kernel_with_causal_rows(B, monkeypatch):
+@pytest.fixture
+def tuning(B):
+    """Launch-policy overrides through tr_set_tuning, all restored afterwards."""
+    names = []
+
+    def set_(name, value):
+        names.append(name)
+        B.tr_set_tuning(name, value)
+
+    yield set_
+    for n in names:
+        B.tr_set_tuning(n, 0)
+
+
+def test_short_query_kernel_with_causal_rows(B, tuning):
     """The key-splitting kernel forced onto queries of up to 40 tokens: several row tiles, causal mask among them."""
-    monkeypatch.setenv("TR_WG_ROWS", "32")
+    tuning("wg_rows", 32)
     cfg = synth.scaled(synth.CONFIGS[3], store_chunks=40, chunk_len_lo=20, chunk_len_hi=90, n_requests=5,
                        chunks_per_request=3, n_q_lo=3, n_q_hi=40)
     store = synth.make_store(cfg)
@@ -570,12 +584,12 @@ def test_sequence_one_pass_without_the_host_copy(B):
 
 
 @pytest.mark.parametrize("piece", [1, 3])
-def test_sequence_one_pass_cut_key_ranges(B, monkeypatch, piece):
+def test_sequence_one_pass_cut_key_ranges(B, tuning, piece):
     """Pieces of one and three key tiles forced onto short sequences: every row tile that walks more than two pieces is
     cut, pieces that hold no visible key for some rows, the merge over tail and document tokens; chunk lengths that
     alternate so that the split count changes more often than the launch can describe (one coarse run instead); the
     half-split layout; a GQA group that does not divide the row tile."""
-    monkeypatch.setenv("TR_BD_PIECE_TILES", str(piece))
+    tuning("bd_piece_tiles", piece)
     cases = [(synth.QWEN2_7B, (70, 1, 129, 33, 64), 37), (synth.LLAMA3_8B, (300, 5, 260), 130),
              (synth.LLAMA3_8B, (200, 40) * 36, 50), (synth.Shape(14, 2, 64, "bf16", 1e6, 1), (250, 90), 25),
              (synth.LLAMA3_8B, (), 700)]

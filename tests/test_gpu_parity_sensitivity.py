@@ -13,6 +13,7 @@ import pytest
 import oracle
 from paper_2410_07590_amd import synth
 from tests import test_gpu_parity as P
+from tests import test_gpu_parity_softmax_range as S
 from tests.test_pins_catch_mistakes import MISTAKES, PY_MISTAKES, SRC, _apply, _build, _package_copy
 
 pytestmark = pytest.mark.gpu
@@ -43,6 +44,8 @@ def _battery(B):
     P.test_decode_batch_ragged(B, 0)
     P.test_linear_against_fp64_matmul(B, 3)
     P.test_linear_against_fp64_matmul(B, 9)
+    S.test_first_visible_keys_in_one_half_of_a_key_step(B)      # logits that do not sit near zero
+    S.test_logits_beyond_the_exponent_range(B)
     for seed in range(3):
         P.test_random_requests(B, seed)
         P.test_random_sequences(B, seed)

@@ -182,6 +182,30 @@ def test_prefill_and_gather_with_moving_logits(B, pattern, shape_no):
     print("%s %s: prefill %.3e, gather %.3e" % (pattern, sh, err, err_g))
 
 
+def test_logits_beyond_the_exponent_range(B):
+    """The first chunk 1100 log2 units below zero and every other key 1100 above (exp of such a score, or of its distance
+    from the first score, overflows even in fp64): only a softmax taken relative to the row maximum, as Sec. 3.1's
+    definition allows, gives a finite result.  Prefill with split keys, gather, decode."""
+    sh = synth.LLAMA3_8B
+    rng = np.random.Generator(np.random.PCG64(4248))
+    store, req = _request(rng, sh, (200, 330, 150), 37, lambda j: np.where(j < 200, -1100.0, 1100.0), synth.POS_REORDERED)
+    s = _request_logits(sh, store, req, np.array([0, 36]))
+    assert s[:, :200].max() < -1050.0 and s[:, 200:req.n_doc + 1].min() > 1050.0
+    sd = B.Store(H.gpu_shape(B, sh), store.k.cuda(), store.v.cuda(), store.row_start)
+    o = H.run_request_oracle(sh, store, req)
+    g = H.run_request_gpu(B, sh, sd, req)
+    err = _rel_check(H.to_f64(g["out"]), o["out"], "prefill, logits near 1100")
+    err_g = _rel_check(H.to_f64(H.run_request_gather_gpu(B, sh, sd, req)), o["out"], "gather, logits near 1100")
+    gs = H.gpu_shape(B, sh)
+    kv = np.array([0, g["kv_len"]], np.int64)
+    dec = torch.full((1, sh.n_q_heads, sh.head_dim), float("nan"), dtype=sh.torch_dtype, device="cuda")
+    B.tr_decode_attn(gs, req.q[-1:].cuda(), g["cache_k"].cuda(), g["cache_v"].cuda(), torch.from_numpy(req.q_pos[-1:]).cuda(), kv, dec,
+                     B.workspace(B.tr_decode_attn_workspace_size(gs, kv)))
+    torch.cuda.synchronize()
+    err_d = _rel_check(H.to_f64(dec), o["out"][-1:], "decode, logits near 1100")
+    print("logits near 1100: prefill %.3e, gather %.3e, decode %.3e" % (err, err_g, err_d))
+
+
 def test_batched_prefill_with_moving_logits(B):
     """Four requests of different lengths and patterns in one launch (the planner cuts each into its own pieces)."""
     sh = synth.QWEN2_7B

@@ -149,6 +149,27 @@ def test_softmax_properties():
     assert np.allclose(oracle.attn_prefix(qq, kk, vv)[0, 0, :4], w, atol=1e-15)
 
 
+def test_softmax_is_exact_for_scores_of_any_size():
+    """Scores hundreds of nats above and below zero, where exp of the score itself overflows or vanishes in fp64: the
+    weights are those of the shifted scores (closed form in extended precision), in any key order."""
+    d = 16
+    qq = np.zeros((1, 1, d)); qq[0, 0, 0] = 1.0
+    for s in ([-3000.0, -2990.5, -2992.0, -3400.0], [800.0, 805.0, -20.0, 803.5, 0.0], [-5.0, 900.0, 899.0], [750.0, 10.0, 751.0]):
+        s = np.array(s)
+        kk = np.zeros((s.size, 1, d)); kk[:, 0, 0] = s * np.sqrt(d)
+        vv = np.zeros((s.size, 1, d)); vv[np.arange(s.size), 0, np.arange(s.size)] = 1.0
+        w = np.exp(s.astype(np.longdouble) - np.longdouble(s.max()))
+        w = (w / w.sum()).astype(np.float64)
+        got = oracle.attn_prefix(qq, kk, vv)[0, 0, :s.size]
+        assert np.isfinite(got).all() and np.allclose(got, w, atol=1e-14)
+        lo = np.zeros(s.size, np.int32)
+        got = oracle.attn_rows(np.repeat(qq, s.size, axis=0), kk, vv, lo, rows=np.array([s.size - 1], np.int32))[0, 0, :s.size]
+        assert np.allclose(got, w, atol=1e-14)
+        cu = np.array([0, s.size], np.int32)
+        got = oracle.attn_blockdiag(np.repeat(qq, s.size, axis=0), kk, vv, cu, rows=np.array([s.size - 1], np.int32))[0, 0, :s.size]
+        assert np.allclose(got, w, atol=1e-14)
+
+
 def test_pipeline_reordered_equals_standard_rope_attention_with_independent_chunks():
     """End to end (Sec. 3.2 + Sec. 3.4): a store built offline from raw keys at chunk-local positions,
     assembled with re-rotation by the chunk offsets, gives the same query output as rotating the raw keys

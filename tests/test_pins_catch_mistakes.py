@@ -34,6 +34,8 @@ MISTAKES = [
     ("values re-rotated like keys", "out_v[dn + e] = load_elem(v_store, so + e, dtype);", "out_v[dn + e] = load_elem(k_store, so + e, dtype);"),
     ("score scale dropped", "double scale = 1.0 / sqrt((double)d);", "double scale = 1.0;"),
     ("score scale 1/d", "double scale = 1.0 / sqrt((double)d);", "double scale = 1.0 / (double)d;"),
+    ("softmax exponent without the row maximum", "scratch[j - lo] = exp(scratch[j - lo] - smax);", "scratch[j - lo] = exp(scratch[j - lo]); (void)smax;"),
+    ("softmax relative to the first score, not the largest", "if (s > smax) smax = s;", "if (j == lo) smax = s;"),
     ("weights not normalised", "double w = scratch[j - lo] / denom;", "double w = scratch[j - lo];"),
     ("query token does not see itself", "0, n_doc + i, scratch", "0, n_doc + i - 1, scratch"),
     ("query token sees its successor", "0, n_doc + i, scratch", "0, (n_doc + i + 1 < kv_len ? n_doc + i + 1 : n_doc + i), scratch"),
