@@ -164,6 +164,19 @@ int tr_prefill_attn(const tr_shape* shape, const void* q, const void* k, const v
                     const int32_t* q_pos /*device*/, int32_t n_q, int64_t kv_len, void* out,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same call for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  tr_prefill_attn's split-KV partial results go to a file-scope device array of
+ * tr_prefill_attn_static_scratch_bytes() = 32 MiB inside the library instead of a caller's workspace (each GPU the
+ * library runs on holds that array until the process ends); the call performs no hipMalloc / hipFree and uses no
+ * allocating library routine.  Arguments, results (bit for bit) and errors as for tr_prefill_attn, plus
+ * TR_ERR_WORKSPACE when the shape needs more scratch than the array holds (then nothing is enqueued; use
+ * tr_prefill_attn).  Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race on it; calls on one stream are ordered and safe.  Nothing in the array has to be cleared between
+ * calls: each call writes every partial row it reads. */
+size_t tr_prefill_attn_static_scratch_bytes(void);
+int tr_prefill_attn_static(const tr_shape* shape, const void* q, const void* k, const void* v,
+                           const int32_t* q_pos /*device*/, int32_t n_q, int64_t kv_len, void* out, void* stream);
+
 /* Batched form (one launch for many requests): q/out packed over requests by cu_q; request r's cache is rows
  * [cache_row_start[r], cache_row_start[r+1]) of k/v (kv_len_r = the range length, its last n_q_r rows are
  * the request's query tokens); q_pos packed like q.  Index arrays are host arrays. */

@@ -22,7 +22,7 @@ TR_ROPE_INTERLEAVED, TR_ROPE_HALF = 0, 1
 EXPORTS = [
     "tr_last_error", "tr_store_create", "tr_store_destroy", "tr_plan",
     "tr_kv_assemble", "tr_kv_assemble_raw", "tr_kv_assemble_batched", "tr_kv_append", "tr_kv_append_batched", "tr_kv_assemble_append",
-    "tr_prefill_attn_workspace_size", "tr_prefill_attn",
+    "tr_prefill_attn_workspace_size", "tr_prefill_attn", "tr_prefill_attn_static_scratch_bytes", "tr_prefill_attn_static",
     "tr_prefill_attn_batched_workspace_size", "tr_prefill_attn_batched",
     "tr_prefill_attn_gather_workspace_size", "tr_prefill_attn_gather",
     "tr_decode_attn_workspace_size", "tr_decode_attn",
@@ -62,7 +62,7 @@ def lib():
         for name in ("tr_prefill_attn_workspace_size", "tr_prefill_attn_batched_workspace_size",
                      "tr_prefill_attn_gather_workspace_size", "tr_decode_attn_workspace_size",
                      "tr_chunk_prefill_attn_workspace_size", "tr_sequence_prefill_attn_workspace_size",
-                     "tr_linear_workspace_size"):
+                     "tr_linear_workspace_size", "tr_prefill_attn_static_scratch_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -204,6 +204,16 @@ def tr_prefill_attn(shape, q, k, v, q_pos, kv_len, out, workspace=None, stream=N
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().tr_prefill_attn(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), C.c_int32(q.shape[0]),
                                  C.c_int64(kv_len), _dev(out), _dev(workspace), C.c_size_t(ws_bytes), _stream(stream)))
+
+
+def tr_prefill_attn_static_scratch_bytes():
+    return int(lib().tr_prefill_attn_static_scratch_bytes())
+
+
+def tr_prefill_attn_static(shape, q, k, v, q_pos, kv_len, out, stream=None):
+    """tr_prefill_attn with the library's own static scratch array instead of a workspace (no device allocation)."""
+    _check(lib().tr_prefill_attn_static(C.byref(shape), _dev(q), _dev(k), _dev(v), _dev(q_pos), C.c_int32(q.shape[0]),
+                                        C.c_int64(kv_len), _dev(out), _stream(stream)))
 
 
 def tr_set_tuning(name, value):

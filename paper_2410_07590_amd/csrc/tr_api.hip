@@ -704,6 +704,56 @@ extern "C" int tr_prefill_attn(const tr_shape* shape, const void* q, const void*
     });
 }
 
+// ---- the same prefill for callers that cannot allocate device memory -------------------------------------------------
+// The split-KV partial results live in a file-scope device array instead of a caller's workspace.  The array's name is a
+// host-side stand-in in host code; its device address is looked up once per device with hipGetSymbolAddress (each GPU
+// holds its own copy) and that pointer is what the kernels get.  Nothing in it has to start at zero: every partial row
+// the merge reads was written by the attention kernel of the same call.
+#define TR_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+#define TR_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char tr_static_scratch[TR_STATIC_SCRATCH_BYTES];
+static std::atomic<void*> g_static_scratch[TR_MAX_DEVICES];
+
+static int static_scratch_ptr(void** out)
+{
+    int dev = 0;
+    TR_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= TR_MAX_DEVICES) return tr_fail(TR_ERR_UNSUPPORTED, "device ordinal %d: at most %d devices", dev, TR_MAX_DEVICES);
+    void* p = g_static_scratch[dev].load(std::memory_order_acquire);
+    if (!p) {
+        TR_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(tr_static_scratch)));
+        if (!p || ((uintptr_t)p & 255) != 0) return tr_fail(TR_ERR_HIP, "the static scratch array has no usable device address");
+        g_static_scratch[dev].store(p, std::memory_order_release); // a race stores the same address twice
+    }
+    *out = p;
+    return TR_OK;
+}
+
+extern "C" size_t tr_prefill_attn_static_scratch_bytes(void) { return TR_STATIC_SCRATCH_BYTES; }
+
+extern "C" int tr_prefill_attn_static(const tr_shape* shape, const void* q, const void* k, const void* v, const int32_t* q_pos,
+                                      int32_t n_q, int64_t kv_len, void* out, void* stream)
+{
+    return tr_guard_int([&]() -> int {
+    tr_clear_error();
+    int rc = tr_check_shape(shape);
+    if (rc) return rc;
+    if (n_q < 0) return tr_fail(TR_ERR_INVALID_ARG, "n_q < 0");
+    if (kv_len < n_q) return tr_fail(TR_ERR_INVALID_ARG, "kv_len %lld < n_q %d: the cache must hold the query tokens", (long long)kv_len, n_q);
+    if (kv_len > ROW_LIMIT) return tr_fail(TR_ERR_UNSUPPORTED, "kv_len of 2^31 or more");
+    if (n_q == 0) return TR_OK;
+    if (!q || !k || !v || !q_pos || !out) return tr_fail(TR_ERR_INVALID_ARG, "tr_prefill_attn_static: NULL pointer");
+    std::vector<ReqGeom> reqs{{0, n_q, 0, kv_len}};
+    const size_t need = prefix_ws_bytes(shape, reqs);
+    if (need > TR_STATIC_SCRATCH_BYTES)
+        return tr_fail(TR_ERR_WORKSPACE, "tr_prefill_attn_static: this shape needs %zu bytes of split-KV scratch, the static array holds %zu; "
+                       "use tr_prefill_attn with a workspace", need, (size_t)TR_STATIC_SCRATCH_BYTES);
+    void* scratch = nullptr;
+    if (need > 0 && (rc = static_scratch_ptr(&scratch))) return rc;
+    return run_prefix(shape, q, k, v, q_pos, reqs, out, scratch, need > 0 ? TR_STATIC_SCRATCH_BYTES : 0, (hipStream_t)stream);
+    });
+}
+
 extern "C" size_t tr_prefill_attn_batched_workspace_size(const tr_shape* shape, const int32_t* cu_q,
                                                          const int64_t* cache_row_start, int32_t n_req)
 {

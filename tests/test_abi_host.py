@@ -240,6 +240,35 @@ def test_prefill_attn_validation_and_workspace(L):
     assert call(n_q=0, kv_len=100) == B.TR_OK
 
 
+def test_static_scratch_prefill_validation_and_size_limit(L):
+    """tr_prefill_attn_static: the same validation as tr_prefill_attn, and a refusal, before any GPU call, of shapes
+    whose split-KV partials exceed the library's static array."""
+    sh = _shape(32, 8, 128, base=5e5)
+    L.tr_prefill_attn_static_scratch_bytes.restype = C.c_size_t
+    cap = L.tr_prefill_attn_static_scratch_bytes()
+    assert cap == 32 << 20
+
+    def call(n_q=1024, kv_len=70000, q=FAKE, out=FAKE, shape=sh):
+        return L.tr_prefill_attn_static(C.byref(shape), q, FAKE, FAKE, FAKE, C.c_int32(n_q), C.c_int64(kv_len), out, None)
+
+    assert call(kv_len=63) == B.TR_ERR_INVALID_ARG
+    assert call(q=None) == B.TR_ERR_INVALID_ARG
+    assert call(out=None) == B.TR_ERR_INVALID_ARG
+    assert call(n_q=-1) == B.TR_ERR_INVALID_ARG
+    assert call(shape=_shape(hq=30)) == B.TR_ERR_SHAPE
+    assert call(n_q=0, kv_len=100) == B.TR_OK
+    # under the default policy a single request at this shape stays below the array's size; four workgroups per CU as
+    # the target cuts it into 8 pieces, 66 MiB of partial results
+    assert L.tr_prefill_attn_workspace_size(C.byref(sh), C.c_int32(1024), C.c_int64(70000)) <= cap
+    assert L.tr_set_tuning(b"target_items", C.c_int32(1024)) == B.TR_OK
+    try:
+        assert L.tr_prefill_attn_workspace_size(C.byref(sh), C.c_int32(1024), C.c_int64(70000)) > cap
+        assert call() == B.TR_ERR_WORKSPACE
+        assert b"static" in L.tr_last_error()
+    finally:
+        assert L.tr_set_tuning(b"target_items", C.c_int32(0)) == B.TR_OK
+
+
 def test_set_tuning_validation_and_effect(L):
     sh = _shape()
     assert L.tr_set_tuning(None, C.c_int32(1)) == B.TR_ERR_INVALID_ARG
