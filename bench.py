@@ -1,18 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the TurboRAG online-prefill hot path on one MI355X.
 
-A step is one pass of the online path for one request of configuration 2 (Qwen2-7B attention
-shape, 8 retrieved chunks x 512 tokens out of a 256-chunk store, 64 query tokens, reordered
-positions): gather plan -> tr_kv_assemble_append (KV gather with RoPE re-rotation, and the query
-tokens' own rows, one launch) -> tr_prefill_attn, one layer.
-Steps cycle through 16 requests with different chunk ids and their own cache buffers, so the
-store is read from HBM rather than from a warm cache.  The K timed steps are captured once in a
-HIP graph (the way a serving loop would issue them) and replayed between two synchronisations;
-`eager_us_per_step` is the same loop driven call by call from Python.
+A step is one pass of the online path for one request of configuration 4 (Llama-3-8B attention
+shape, 32 chunks x 1024 tokens, 256 query tokens, reordered positions), one layer: gather plan ->
+tr_kv_assemble_append (KV gather with RoPE re-rotation, and the query tokens' own rows, one
+launch) -> tr_prefill_attn.  Steps cycle through 4 requests with different chunk orders, their own
+cache buffers and two copies of the store, so that the store is read from HBM rather than from a
+warm cache.  The K timed steps are captured once in a HIP graph (the way a serving loop would
+issue them) and replayed between two synchronisations; `eager_us_per_step` is the same loop driven
+call by call from Python, host-side plan included.
 
-The JSON line also carries the roofline of the dominant kernel of the step, the rooflines of the
-other kernels at the sizes where they are bandwidth- or MFMA-bound (configurations 4 and 5), and
-the CPU oracle timed on the host cores.
+The JSON line starts with a summary (kernel@workload -> [us, fraction of peak, bound]) and also
+carries the roofline of the dominant kernel of the step, the rooflines of the other kernels at
+the sizes where they are bandwidth- or MFMA-bound (configurations 2, 3 and 5, the one-pass
+sequence form, decode, short queries), what a plain copy and a bare matrix-instruction loop reach
+on the same GPU in the same run, and the CPU oracle timed on the host cores.
 """
 import argparse
 import gc
@@ -25,26 +27,6 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
-N_VARIANTS = 16
-
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters read
-# on a copy kernel of known size (the summaries are under profiles/).  None where not measured.
-MEASURED_TRAFFIC = {
-    ("tr_prefill_attn", "qwen2-7b-8x512-q64"): 23833624,       # prefix_attn 16.5 MB (6.2 MB of split partials written) + combine 7.3 MB
-    ("tr_kv_assemble", "qwen2-7b-8x512-q64"): 16961808,
-    ("tr_kv_assemble", "llama3-8b-32x1024-q256"): 268702185,
-    ("tr_prefill_attn", "llama3-8b-32x1024-q256"): 174881462,  # prefix_attn 154.9 MB + combine 20.0 MB
-    ("tr_chunk_prefill_attn", "offline-64x512"): 808601553,    # table 0.6 MB + key rotation 135.7 MB + attention 672.4 MB
-    ("tr_decode_attn", "decode-64x4096-qwen2-7b"): 537985990,
-    ("tr_kv_assemble_append", "qwen2-7b-8x512-q64"): 17439921,
-    ("tr_kv_assemble_raw", "llama3-8b-32x1024-q256"): 268752804,
-    ("tr_kv_assemble_batched", "batched-serving-16req"): 408274047,
-    ("tr_prefill_attn_batched", "batched-serving-16req"): 329371660,    # prefix_attn 275.9 MB + combine 53.4 MB
-    ("tr_sequence_prefill_attn", "32x1024-chunks-plus-256-query-llama3-8b"): 1085821232,  # key rotation 136.6 MB + attention 929.2 MB + combine 20.0 MB
-    ("tr_linear", "qwen2-7b-qkv-projection-64-tokens"): 51639534,      # linear_kernel 43.9 MB (7.1 MB of partial sums written) + merge 7.7 MB
-    ("tr_linear", "qwen2-7b-output-projection-64-tokens"): 42858412,   # linear_kernel 35.9 MB (6.4 MB of partial sums written) + merge 6.9 MB
-}
-
 
 def _events(torch, n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
@@ -75,20 +57,46 @@ def _time_calls(torch, fn, iters, warmup=3, reps=5):
     return float(np.mean(ts)), float(ts[len(ts) // 2]), float(ts[0])
 
 
+def source_digest():
+    """SHA-256 over the kernel sources: counter figures measured on other kernels than these are not reported."""
+    import hashlib
+    here = os.path.dirname(os.path.abspath(__file__))
+    csrc = os.path.join(here, "paper_2410_07590_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(f for f in os.listdir(csrc) if f.endswith((".hip", ".h"))):
+        h.update(name.encode())
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def load_traffic():
+    """HBM bytes per launch from the rocprofv3 counter runs summarised under profiles/ (written there by
+    `python -m paper_2410_07590_amd.profile_summary`).  Empty when the kernels have changed since they were taken."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return {}, None
+    if rec.get("csrc_sha256") != source_digest():
+        return {}, None
+    return rec.get("bytes_per_launch", {}), rec.get("commit")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--no-extra", action="store_true", help="skip configurations 4/5 and the CPU baseline")
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the CPU baseline")
     ap.add_argument("--no-graph", action="store_true", help="time the eager loop instead of a HIP graph replay")
     ap.add_argument("--host-store", action="store_true",
-                    help="also time the path with the chunk store in pinned host memory (PCIe-bound; kept out of the default "
-                         "run so that its slow launches of the same kernels do not blur the kernel trace)")
+                    help="time the host-resident store over all 28 layers, three times (the default run does 8 layers once)")
     ap.add_argument("--case", default=None,
                     help="profiling aid: run only one kernel path --iters times, eagerly, and print nothing but a note "
-                         "(step2, assemble2, asmapp2, attn2, assemble4, raw4, attn4, batched3, offline5, sequence4, decode2, linear2, "
-                         "linearqkv2, copy)")
+                         "(step2, assemble2, asmapp2, attn2, step4, assemble4, asmapp4, raw4, attn4, batched3, offline5, sequence4, "
+                         "decode2, shortq, shortq16, linear2, linearqkv2, copy, mfmaloop)")
     ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -111,22 +119,102 @@ def main():
         run_case(torch, B, synth, args.case, args.iters)
         return
 
-    # ------------------------------------------------------------------ configuration 2 workload
-    cfg = synth.CONFIGS[2]
+    traffic, traffic_commit = load_traffic()
+
+    def hbm_roof(name, workload, nbytes, t_us):
+        a = nbytes / (t_us[0] * 1e-6) / 1e9
+        return {"kernel": name, "workload": workload, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4), "traffic": traffic.get("%s@%s" % (name, workload)),
+                "avg_us": round(t_us[0], 2), "median_us": round(t_us[1], 2), "algorithmic_bytes": nbytes}
+
+    def mfma_roof(name, workload, flops, t_us, nbytes):
+        a = flops / (t_us[0] * 1e-6) / 1e12
+        return {"kernel": name, "workload": workload, "bound": "mfma", "achieved": round(a, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(a / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic.get("%s@%s" % (name, workload)),
+                "avg_us": round(t_us[0], 2), "median_us": round(t_us[1], 2), "algorithmic_flops": flops,
+                "algorithmic_bytes": nbytes, "hbm_gbs": round(nbytes / (t_us[0] * 1e-6) / 1e9, 1)}
+
+    # headline: the step at configuration 4, the largest single-GPU configuration
+    cfg = synth.CONFIGS[4]
+    head = bench_step(torch, B, synth, acct, cfg, N_VARIANTS[4], args.steps, args.warmup, args.no_graph, hbm_roof, mfma_roof)
+    us_per_step = head["eager_us"] if args.no_graph else head["graph_us"]
+    sh = cfg.shape
+    result = {
+        "summary": None,   # filled below; first, so that a truncated record keeps every kernel's figure
+        "metric": "us/layer query-prefill over assembled KV (gather plan + assemble and append + prefill attention); `value` is a "
+                  "HIP-graph replay of the K steps, which holds the kernels only: the host-side plan and argument marshalling "
+                  "ran at capture; eager_us_per_step is the same K steps driven call by call from Python, plan included",
+        "value": round(us_per_step, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_per_step / 1e3, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 4: %s (%d q heads, %d kv heads, head_dim %d, 32 chunks x 1024 tokens, 256 query tokens, reordered positions)"
+                               % (cfg.name, sh.n_q_heads, sh.n_kv_heads, sh.head_dim),
+                   "timed_as": "eager" if args.no_graph else "hip_graph_replay", "request_variants": N_VARIANTS[4]},
+        "eager_us_per_step": round(head["eager_us"], 3),
+        "kernel_us": head["kernel_us"],
+        "roofline": head["roofline"],
+        "traffic_measured_at_commit": traffic_commit,
+    }
+    roof_extra = head["roof_extra"]
+
+    if not args.no_extra:
+        c2 = bench_step(torch, B, synth, acct, synth.CONFIGS[2], N_VARIANTS[2], 256, 16, args.no_graph, hbm_roof, mfma_roof)
+        roof_extra.append({"kernel": "step (assemble and append + prefill attention)", "workload": synth.CONFIGS[2].name,
+                           "graph_replay_us": round(c2["graph_us"], 2), "eager_us": round(c2["eager_us"], 2), "steps": 256,
+                           "kernel_us": c2["kernel_us"]})
+        roof_extra += [c2["roofline"]] + c2["roof_extra"]
+        roof_extra += bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof)
+        roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
+        roof_extra += bench_sequence(torch, B, synth, acct, mfma_roof)
+        roof_extra += bench_decode(torch, B, synth, hbm_roof)
+        roof_extra += bench_short_query(torch, B, synth, hbm_roof)
+        roof_extra += bench_host_store(torch, B, synth, acct, *((H2D_LAYERS, 3) if args.host_store else (8, 1)))
+        result["layer_context"], lin_roofs = bench_layer_context(torch, B, synth, hbm_roof)
+        roof_extra += lin_roofs
+        result["table4_batch_scaling"] = bench_table4_batches(torch, B, synth)
+        ceil = {"hbm_copy_gbs": measured_copy_rate(torch)}
+        ceil.update(measured_mfma_loop(torch, B))
+        result["measured_ceilings"] = ceil
+        result["hbm_copy_ceiling_gbs"] = ceil["hbm_copy_gbs"]
+        for r in [result["roofline"]] + roof_extra:   # the same fractions against what the chip delivered in this run
+            if r.get("bound") == "mfma":
+                r["frac_of_measured_loop"] = round(r["achieved"] / ceil["mfma_loop_tflops_random_operands"], 4)
+            elif r.get("bound") == "hbm":
+                r["frac_of_measured_copy"] = round(r["achieved"] / ceil["hbm_copy_gbs"], 4)
+        result["cpu_baseline"] = cpu_baseline(synth, cfg)
+    result["roofline_extra"] = roof_extra
+    result["summary"] = {"%s@%s" % (r["kernel"], r["workload"]): [r["avg_us"], r["frac"], r["bound"]]
+                         for r in [result["roofline"]] + roof_extra if "frac" in r and "avg_us" in r}
+    print(json.dumps(result))
+
+
+N_VARIANTS = {2: 16, 4: 4}
+
+
+def bench_step(torch, B, synth, acct, cfg, n_variants, steps, warmup, eager_only, hbm_roof, mfma_roof):
+    """The step (gather plan -> tr_kv_assemble_append -> tr_prefill_attn, one layer) for one request of `cfg`.
+    Steps cycle through n_variants requests with different chunk ids, their own cache buffers and one of two copies
+    of the store, so that a step reads its chunks from HBM rather than from a warm cache."""
     sh = cfg.shape
     gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
     store = synth.make_store(cfg)
-    sd = B.Store(gs, store.k.cuda(), store.v.cuda(), store.row_start)
+    stores = [B.Store(gs, store.k.cuda(), store.v.cuda(), store.row_start) for _ in range(2)]
     base_req = synth.make_requests(cfg, store)[0]
     rng = synth.rng_for(cfg, 9)
     variants = []
-    for i in range(N_VARIANTS):
-        ids = base_req.chunk_ids if i == 0 else rng.choice(cfg.store_chunks, size=cfg.chunks_per_request, replace=False).astype(np.int32)
+    for i in range(n_variants):
+        if i == 0:
+            ids = base_req.chunk_ids
+        elif cfg.id_draw == "shuffle_all":
+            ids = rng.permutation(cfg.store_chunks).astype(np.int32)
+        else:
+            ids = rng.choice(cfg.store_chunks, size=cfg.chunks_per_request, replace=False).astype(np.int32)
+        sd = stores[i % 2]
         offsets, _ = B.tr_plan(sd, ids, base_req.pos_mode, want_pos_ids=False)
         n_doc = int(offsets[-1])
         kv_len = n_doc + base_req.n_q
         variants.append(dict(
-            ids=ids, n_doc=n_doc, kv_len=kv_len,
+            sd=sd, ids=ids, n_doc=n_doc, kv_len=kv_len,
             cache_k=torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda"),
             cache_v=torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda"),
             out=torch.empty((base_req.n_q, sh.n_q_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda")))
@@ -136,8 +224,12 @@ def main():
     ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, n_q, variants[0]["kv_len"]))
 
     def assemble(v):
-        offsets, _ = B.tr_plan(sd, v["ids"], base_req.pos_mode, want_pos_ids=False)   # a1: plan (host)
-        B.tr_kv_assemble(sd, v["ids"], offsets, base_req.pos_mode, v["cache_k"], v["cache_v"])
+        offsets, _ = B.tr_plan(v["sd"], v["ids"], base_req.pos_mode, want_pos_ids=False)   # the gather plan (host)
+        B.tr_kv_assemble(v["sd"], v["ids"], offsets, base_req.pos_mode, v["cache_k"], v["cache_v"])
+
+    def assemble_raw(v):   # the same bytes moved from a store read as un-rotated keys, each turned once at its position id
+        offsets, _ = B.tr_plan(v["sd"], v["ids"], base_req.pos_mode, want_pos_ids=False)
+        B.tr_kv_assemble_raw(v["sd"], v["ids"], offsets, base_req.pos_mode, v["cache_k"], v["cache_v"])
 
     def append(v):
         B.tr_kv_append(gs, k_q, v_q, q_pos, v["cache_k"], v["cache_v"], v["n_doc"])
@@ -146,115 +238,74 @@ def main():
         B.tr_prefill_attn(gs, q, v["cache_k"], v["cache_v"], q_pos, v["kv_len"], v["out"], ws)
 
     def assemble_append(v):
-        offsets, _ = B.tr_plan(sd, v["ids"], base_req.pos_mode, want_pos_ids=False)   # a1: plan (host)
-        B.tr_kv_assemble_append(sd, v["ids"], offsets, base_req.pos_mode, k_q, v_q, q_pos, v["cache_k"], v["cache_v"])
+        offsets, _ = B.tr_plan(v["sd"], v["ids"], base_req.pos_mode, want_pos_ids=False)   # the gather plan (host)
+        B.tr_kv_assemble_append(v["sd"], v["ids"], offsets, base_req.pos_mode, k_q, v_q, q_pos, v["cache_k"], v["cache_v"])
 
     def step(i):
-        v = variants[i % N_VARIANTS]
+        v = variants[i % n_variants]
         assemble_append(v)
         attn(v)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
 
     # eager loop (host-driven).  Python's cyclic collector is paused for it: with torch loaded one full collection
-    # takes about 40 ms, a thousand steps' worth, and it would fire a few times inside the loop.
+    # takes about 40 ms, many steps' worth, and it would fire a few times inside the loop.
     gc.collect()
     gc.disable()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
-    eager_s = time.perf_counter() - t0
+    eager_us = (time.perf_counter() - t0) / steps * 1e6
     gc.enable()
 
-    if args.no_graph:
-        total_s = eager_s
-    else:
+    graph_us = None
+    if not eager_only:
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            for i in range(args.steps):
+            for i in range(steps):
                 step(i)
         graph.replay()               # untimed: first replay uploads the graph
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         graph.replay()
         torch.cuda.synchronize()
-        total_s = time.perf_counter() - t0
-    us_per_step = total_s / args.steps * 1e6
+        graph_us = (time.perf_counter() - t0) / steps * 1e6
 
-    # ------------------------------------------------------------------ per-kernel durations, HIP events
-    it = 64
+    # per-kernel durations, HIP events around graph replays
+    it = 64 if cfg.number == 2 else 24
     cyc = {"i": 0}
 
     def cyc_call(fn):
         def f():
             cyc["i"] += 1
-            fn(variants[cyc["i"] % N_VARIANTS])
+            fn(variants[cyc["i"] % n_variants])
         return f
 
     t_asm = _time_calls(torch, cyc_call(assemble), it)
     t_app = _time_calls(torch, cyc_call(append), it)
-    t_asa = _time_calls(torch, cyc_call(assemble_append), it)
+    t_raw = _time_calls(torch, cyc_call(assemble_raw), it) if cfg.number == 4 else None
+    t_asa = _time_calls(torch, cyc_call(assemble_append), it)   # last: the caches hold the pre-rotated store's rows again
     t_att = _time_calls(torch, cyc_call(attn), it)
 
-    kv_len = variants[0]["kv_len"]
+    kv_len, n_doc = variants[0]["kv_len"], variants[0]["n_doc"]
     eb = sh.elem_bytes
-    asm_bytes = acct.assemble_bytes(variants[0]["n_doc"], sh.n_kv_heads, sh.head_dim, eb)
+    asm_bytes = acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb)
     att_flops = acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_prefix(n_q, kv_len))
     att_bytes = acct.prefill_attn_bytes(n_q, kv_len, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb)
-
-    def hbm_roof(name, workload, nbytes, t_us):
-        a = nbytes / (t_us[0] * 1e-6) / 1e9
-        return {"kernel": name, "workload": workload, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((name, workload)),
-                "avg_us": round(t_us[0], 2), "median_us": round(t_us[1], 2), "algorithmic_bytes": nbytes}
-
-    def mfma_roof(name, workload, flops, t_us, nbytes):
-        a = flops / (t_us[0] * 1e-6) / 1e12
-        return {"kernel": name, "workload": workload, "bound": "mfma", "achieved": round(a, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(a / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get((name, workload)),
-                "avg_us": round(t_us[0], 2), "median_us": round(t_us[1], 2), "algorithmic_flops": flops,
-                "algorithmic_bytes": nbytes, "hbm_gbs": round(nbytes / (t_us[0] * 1e-6) / 1e9, 1)}
-
     # dominant kernel of the step: query-prefill attention (prefix_attn_kernel + its split-KV combine)
     roofline = mfma_roof("tr_prefill_attn", cfg.name, att_flops, t_att, att_bytes)
     asa_bytes = asm_bytes + acct.append_bytes(n_q, sh.n_kv_heads, sh.head_dim, eb)
     roof_extra = [hbm_roof("tr_kv_assemble_append", cfg.name, asa_bytes, t_asa),
                   hbm_roof("tr_kv_assemble", cfg.name, asm_bytes, t_asm),
                   {"kernel": "tr_kv_append", "workload": cfg.name, "avg_us": round(t_app[0], 2), "median_us": round(t_app[1], 2)}]
-
-    result = {
-        "metric": "us/layer query-prefill over assembled KV (plan + assemble and append + prefill attention)",
-        "value": round(us_per_step, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(us_per_step / 1e3, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "config 2: %s (28 q heads, 4 kv heads, head_dim 128, 8 of 256 chunks x 512 tokens, 64 query tokens, reordered positions)" % cfg.name,
-                   "timed_as": "eager" if args.no_graph else "hip_graph_replay", "request_variants": N_VARIANTS},
-        "eager_us_per_step": round(eager_s / args.steps * 1e6, 3),
-        "kernel_us": {"assemble_append": round(t_asa[0], 2), "prefill_attn": round(t_att[0], 2),
-                      "assemble_alone": round(t_asm[0], 2), "append_alone": round(t_app[0], 2)},
-        "roofline": roofline,
-    }
-
-    if not args.no_extra:
-        del sd, store
-        roof_extra += bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof)
-        roof_extra += bench_config3(torch, B, synth, acct, hbm_roof, mfma_roof)
-        roof_extra += bench_config5(torch, B, synth, acct, mfma_roof)
-        roof_extra += bench_sequence(torch, B, synth, acct, mfma_roof)
-        roof_extra += bench_decode(torch, B, synth, hbm_roof)
-        roof_extra += bench_short_query(torch, B, synth, hbm_roof)
-        if args.host_store:
-            roof_extra += bench_host_store(torch, B, synth, acct)
-        result["layer_context"], lin_roofs = bench_layer_context(torch, B, synth, hbm_roof)
-        roof_extra += lin_roofs
-        result["table4_batch_scaling"] = bench_table4_batches(torch, B, synth)
-        result["hbm_copy_ceiling_gbs"] = measured_copy_rate(torch)
-        result["cpu_baseline"] = cpu_baseline(synth, cfg)
-    result["roofline_extra"] = roof_extra
-    print(json.dumps(result))
+    if t_raw:
+        roof_extra.append(hbm_roof("tr_kv_assemble_raw", cfg.name, asm_bytes, t_raw))
+    kernel_us = {"assemble_append": round(t_asa[0], 2), "prefill_attn": round(t_att[0], 2),
+                 "assemble_alone": round(t_asm[0], 2), "append_alone": round(t_app[0], 2)}
+    return {"graph_us": graph_us, "eager_us": eager_us, "kernel_us": kernel_us, "roofline": roofline, "roof_extra": roof_extra}
 
 
 def run_case(torch, B, synth, case, iters):
@@ -293,6 +344,21 @@ def run_case(torch, B, synth, case, iters):
             B.tr_linear(x, w, y, ws)
         torch.cuda.synchronize()
         print("case linearqkv2: %d calls" % iters)
+        return
+    if case == "mfmaloop":
+        sink = torch.empty(B.tr_probe_mfma_loop_sink_bytes() // 4, dtype=torch.float32, device="cuda")
+        for _ in range(iters):
+            B.tr_probe_mfma_loop(30000, 0, sink)
+            B.tr_probe_mfma_loop(30000, 1, sink)
+        torch.cuda.synchronize()
+        print("case mfmaloop: %d launches with constant and %d with random operands, 30000 loop trips each" % (iters, iters))
+        return
+    if case in ("shortq", "shortq16"):
+        att, _ = _short_query_setup(torch, B, synth, 16 if case == "shortq16" else 1)
+        for _ in range(iters):
+            att()
+        torch.cuda.synchronize()
+        print("case %s: %d calls" % (case, iters))
         return
     if case == "batched3":
         _, _, asm, app, att = _config3_setup(torch, B, synth)
@@ -356,53 +422,6 @@ def run_case(torch, B, synth, case, iters):
             f()
     torch.cuda.synchronize()
     print("case %s: %d iterations" % (case, iters))
-
-
-def bench_config4(torch, B, synth, acct, hbm_roof, mfma_roof):
-    cfg = synth.CONFIGS[4]
-    sh = cfg.shape
-    gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
-    store = synth.make_store(cfg)
-    sd = B.Store(gs, store.k.cuda(), store.v.cuda(), store.row_start)
-    req = synth.make_requests(cfg, store)[0]
-    offsets, _ = B.tr_plan(sd, req.chunk_ids, req.pos_mode, want_pos_ids=False)
-    n_doc, kv_len = int(offsets[-1]), int(offsets[-1]) + req.n_q
-    caches = [(torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda"),
-               torch.empty((kv_len, sh.n_kv_heads, sh.head_dim), dtype=sh.torch_dtype, device="cuda")) for _ in range(2)]
-    q, k_q, v_q = req.q.cuda(), req.k_q.cuda(), req.v_q.cuda()
-    q_pos = torch.from_numpy(req.q_pos).cuda()
-    out = torch.empty(q.shape, dtype=sh.torch_dtype, device="cuda")
-    ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, req.n_q, kv_len))
-    c = {"i": 0}
-
-    def asm():
-        c["i"] += 1
-        ck, cv = caches[c["i"] % 2]
-        B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
-
-    def att():
-        c["i"] += 1
-        ck, cv = caches[c["i"] % 2]
-        B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
-
-    for ck, cv in caches:
-        B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
-        B.tr_kv_append(gs, k_q, v_q, q_pos, ck, cv, n_doc)
-    def asm_raw():   # the same bytes moved from a store that is read as un-rotated keys, each turned once at its position id
-        c["i"] += 1
-        ck, cv = caches[c["i"] % 2]
-        B.tr_kv_assemble_raw(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
-
-    t_asm = _time_calls(torch, asm, 30)
-    t_raw = _time_calls(torch, asm_raw, 30)
-    for ck, cv in caches:   # the attention below reads the cache formed from the pre-rotated store
-        B.tr_kv_assemble(sd, req.chunk_ids, offsets, req.pos_mode, ck, cv)
-    t_att = _time_calls(torch, att, 30)
-    eb = sh.elem_bytes
-    return [hbm_roof("tr_kv_assemble", cfg.name, acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb), t_asm),
-            hbm_roof("tr_kv_assemble_raw", cfg.name, acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, eb), t_raw),
-            mfma_roof("tr_prefill_attn", cfg.name, acct.attn_flops(sh.n_q_heads, sh.head_dim, acct.visible_pairs_prefix(req.n_q, kv_len)),
-                      t_att, acct.prefill_attn_bytes(req.n_q, kv_len, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, eb))]
 
 
 def _config3_setup(torch, B, synth):
@@ -599,10 +618,11 @@ def bench_layer_context(torch, B, synth, hbm_roof):
             "rows": rows}, roofs
 
 
-def bench_short_query(torch, B, synth, hbm_roof):
-    """A few query tokens over a long context (the shape of the paper's Table 2 workloads: 7.5k-16k context tokens,
-    6-20 query tokens): 16 query tokens over 12288 document rows, Qwen2-7B heads.  Every key is read once, so the row
-    is priced against HBM; twelve caches are cycled so that the keys do not sit in the last-level cache."""
+def _short_query_setup(torch, B, synth, n_req):
+    """A few query tokens over a long context (the shape of the paper's Table 2 workloads, Sec. 4.4: 7.5k-16k context
+    tokens, 6-20 query tokens): n_req requests of 16 query tokens over 12288 document rows each, Qwen2-7B heads.
+    Every key is read once, so the rows are priced against HBM; enough caches are cycled that the keys do not sit in
+    the last-level cache."""
     sh = synth.QWEN2_7B
     gs = B.make_shape(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, sh.rope_base)
     gen = torch.Generator(device="cuda")
@@ -610,21 +630,38 @@ def bench_short_query(torch, B, synth, hbm_roof):
     rnd = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     n_q, n_doc = 16, 12288
     kv_len = n_doc + n_q
-    caches = [(rnd(kv_len, sh.n_kv_heads, sh.head_dim), rnd(kv_len, sh.n_kv_heads, sh.head_dim)) for _ in range(12)]
-    q = rnd(n_q, sh.n_q_heads, sh.head_dim)
+    n_caches = 12 if n_req == 1 else 2
+    caches = [(rnd(n_req * kv_len, sh.n_kv_heads, sh.head_dim), rnd(n_req * kv_len, sh.n_kv_heads, sh.head_dim)) for _ in range(n_caches)]
+    q = rnd(n_req * n_q, sh.n_q_heads, sh.head_dim)
     out = torch.empty_like(q)
-    q_pos = torch.arange(n_doc, kv_len, dtype=torch.int32, device="cuda")
-    ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, n_q, kv_len))
+    q_pos = torch.arange(n_doc, kv_len, dtype=torch.int32, device="cuda").repeat(n_req)
+    cu_q = (np.arange(n_req + 1) * n_q).astype(np.int32)
+    crs = np.arange(n_req + 1, dtype=np.int64) * kv_len
+    if n_req == 1:
+        ws = B.workspace(B.tr_prefill_attn_workspace_size(gs, n_q, kv_len))
+    else:
+        ws = B.workspace(B.tr_prefill_attn_batched_workspace_size(gs, cu_q, crs))
     c = {"i": 0}
 
     def att():
         c["i"] += 1
         ck, cv = caches[c["i"] % len(caches)]
-        B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
+        if n_req == 1:
+            B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws)
+        else:
+            B.tr_prefill_attn_batched(gs, q, ck, cv, q_pos, cu_q, crs, out, ws)
 
-    t = _time_calls(torch, att, 24)
-    nbytes = 2 * kv_len * sh.n_kv_heads * sh.head_dim * 2 + 2 * n_q * sh.n_q_heads * sh.head_dim * 2
-    return [hbm_roof("tr_prefill_attn", "short-query-16-tokens-over-12288-rows-qwen2-7b", nbytes, t)]
+    nbytes = n_req * (2 * kv_len * sh.n_kv_heads * sh.head_dim * 2 + 2 * n_q * sh.n_q_heads * sh.head_dim * 2)
+    return att, nbytes
+
+
+def bench_short_query(torch, B, synth, hbm_roof):
+    rows = []
+    for n_req, name, kernel in ((1, "short-query-16-tokens-over-12288-rows-qwen2-7b", "tr_prefill_attn"),
+                                (16, "short-query-16req-x-16-tokens-over-12288-rows-qwen2-7b", "tr_prefill_attn_batched")):
+        att, nbytes = _short_query_setup(torch, B, synth, n_req)
+        rows.append(hbm_roof(kernel, name, nbytes, _time_calls(torch, att, 24 if n_req == 1 else 12)))
+    return rows
 
 
 def bench_table4_batches(torch, B, synth):
@@ -698,10 +735,10 @@ H2D_LAYERS = 28
 PCIE_PEAK_GBS = 63.0   # PCIe 5.0 x16, per direction, after encoding
 
 
-def bench_host_store(torch, B, synth, acct):
+def bench_host_store(torch, B, synth, acct, layers, reps):
     """Host-resident store (the chunk caches stay in pinned host memory, as in the paper's end-to-end runs): the
-    assemble kernel reads the chunks across PCIe and writes the rotated cache rows in one pass.  28 layers of
-    configuration 2, the same request each layer; `serial` runs assemble+append and attention of a layer back to back
+    assemble kernel reads the chunks across PCIe and writes the rotated cache rows in one pass.  `layers` layers of
+    configuration 2 (Sec. 4.5, Table 4's "with h2d" column), the same request each layer, `reps` times; `serial` runs assemble+append and attention of a layer back to back
     on one stream, `overlapped` assembles layer l+1 on a second stream while layer l's attention runs (two cache
     buffers).  Eager launches, wall clock."""
     cfg = synth.CONFIGS[2]
@@ -731,14 +768,14 @@ def bench_host_store(torch, B, synth, acct):
         B.tr_prefill_attn(gs, q, ck, cv, q_pos, kv_len, out, ws, stream=stream)
 
     def serial():
-        for l in range(H2D_LAYERS):
+        for l in range(layers):
             fetch(l, main)
             attend(l, main)
 
     def overlapped():
         for e in free:
             e.record(main)
-        for l in range(H2D_LAYERS):
+        for l in range(layers):
             side.wait_event(free[l % 2])
             fetch(l, side)
             ready[l % 2].record(side)
@@ -753,17 +790,17 @@ def bench_host_store(torch, B, synth, acct):
         gc.collect()
         gc.disable()
         t0 = time.perf_counter()
-        for _ in range(3):
+        for _ in range(reps):
             fn()
         torch.cuda.synchronize()
-        res[name] = (time.perf_counter() - t0) / (3 * H2D_LAYERS) * 1e6
+        res[name] = (time.perf_counter() - t0) / (reps * layers) * 1e6
         gc.enable()
     nbytes = acct.assemble_bytes(n_doc, sh.n_kv_heads, sh.head_dim, sh.elem_bytes) // 2   # bytes that cross PCIe per layer
     rate = nbytes / (res["overlapped"] * 1e-6) / 1e9
     return [{"kernel": "tr_kv_assemble_append + tr_prefill_attn, host-resident store", "workload": cfg.name, "bound": "pcie",
              "achieved": round(rate, 1), "peak": PCIE_PEAK_GBS, "unit": "GB/s", "frac": round(rate / PCIE_PEAK_GBS, 4),
              "us_per_layer_serial": round(res["serial"], 1), "us_per_layer_overlapped": round(res["overlapped"], 1),
-             "pcie_bytes_per_layer": nbytes, "layers": H2D_LAYERS,
+             "pcie_bytes_per_layer": nbytes, "layers": layers, "reps": reps,
              "note": "PCIe-inclusive; never part of `value`, which is measured with the store resident in HBM"}]
 
 
@@ -776,28 +813,43 @@ def measured_copy_rate(torch):
     return round(2 * src.numel() / (t[0] * 1e-6) / 1e9, 1)
 
 
-def cpu_baseline(synth, cfg, budget_s=10.0):
-    """The CPU oracle as it stands on whole requests of configuration 2 (the whole step each, not a sample of it):
-    the request variants in turn for about budget_s seconds of CPU work; the median per request is reported."""
+def measured_mfma_loop(torch, B):
+    """What a bare loop of the attention kernels' matrix instruction reaches on this GPU in this run (TFLOP/s): 8
+    waves on every compute unit, operands from LDS, no softmax and no memory traffic.  Constant operands, and bf16
+    operands of random sign and mantissa; the second is the ceiling attention over real data is up against."""
+    sink = torch.empty(B.tr_probe_mfma_loop_sink_bytes() // 4, dtype=torch.float32, device="cuda")
+    res = {}
+    for key, rnd in (("mfma_loop_tflops_constant_operands", 0), ("mfma_loop_tflops_random_operands", 1)):
+        B.tr_probe_mfma_loop(2000, rnd, sink)
+        torch.cuda.synchronize()
+        rates = []
+        for _ in range(3):
+            e0, e1 = _events(torch, 2)
+            e0.record()
+            flops = B.tr_probe_mfma_loop(30000, rnd, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            rates.append(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        res[key] = round(sorted(rates)[1], 1)
+    return res
+
+
+def cpu_baseline(synth, cfg):
+    """The CPU oracle as it stands on one whole request of the headline configuration (the whole step: plan,
+    assemble, append, attention), timed once."""
     import oracle
     store = synth.make_store(cfg)
-    reqs = synth.make_requests(cfg, store)
+    req = synth.make_requests(cfg, store)[0]
     bits = synth.as_oracle_array
     ks, vs = bits(store.k), bits(store.v)
-    times = []
-    t_start = time.perf_counter()
-    while len(times) < 3 or (time.perf_counter() - t_start < budget_s and len(times) < 400):
-        req = reqs[len(times) % len(reqs)]
-        qb, kqb, vqb = bits(req.q), bits(req.k_q), bits(req.v_q)
-        t0 = time.perf_counter()
-        oracle.online_prefill(ks, vs, store.row_start, req.chunk_ids, req.pos_mode, qb, kqb, vqb, req.q_pos, cfg.shape.rope_base)
-        times.append(time.perf_counter() - t0)
-    times.sort()
-    med = times[len(times) // 2]
-    return {"value": round(med * 1e6, 1), "unit": "us/layer", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%d full requests of configuration 2 in %.1f s (plan, assemble, append, attention; median per request, "
-                      "fastest %.0f us); fp64, attention loops on all threads, gather and RoPE single-threaded"
-                      % (len(times), sum(times), times[0] * 1e6)}
+    qb, kqb, vqb = bits(req.q), bits(req.k_q), bits(req.v_q)
+    t0 = time.perf_counter()
+    oracle.online_prefill(ks, vs, store.row_start, req.chunk_ids, req.pos_mode, qb, kqb, vqb, req.q_pos, cfg.shape.rope_base)
+    dt = time.perf_counter() - t0
+    return {"value": round(dt * 1e6, 1), "unit": "us/layer", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "one full request of configuration %d in %.1f s (plan, assemble, append, attention over %d keys for %d "
+                      "query tokens); fp64, attention loops on all threads, gather and RoPE single-threaded"
+                      % (cfg.number, dt, int(req.n_doc + req.n_q), int(req.n_q))}
 
 
 if __name__ == "__main__":

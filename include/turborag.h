@@ -281,6 +281,17 @@ int tr_linear(const void* x, int32_t M, int32_t K, int32_t n_out, const void* co
  * concurrent use with running calls.  Errors: TR_ERR_INVALID_ARG (unknown name, negative value). */
 int tr_set_tuning(const char* name, int32_t value);
 
+/* Measurement aid, not a step of the method: the rate at which this chip issues the matrix instruction of the
+ * attention kernels (v_mfma_f32_32x32x16_bf16, operands read from LDS, 8 waves on each of the 256 compute units, no
+ * softmax, no global memory traffic).  A caller times the launch with events on `stream` and divides *flops (host,
+ * out: multiply-adds x 2 of the launch) by the duration: that is the ceiling the MFMA-bound rows of a roofline are
+ * really up against, next to the published peak.  random_operands != 0 fills the operands with bf16 values of random
+ * sign and mantissa (magnitude 0.5..4), the kind of data attention feeds the instruction; 0 uses a few constants,
+ * which draw less power and clock higher.  sink: device, at least tr_probe_mfma_loop_sink_bytes() bytes, overwritten.
+ * iters: loop trips of 8 instructions per wave, 1 .. 2^24.  Errors: TR_ERR_INVALID_ARG, TR_ERR_HIP. */
+size_t tr_probe_mfma_loop_sink_bytes(void);
+int tr_probe_mfma_loop(int32_t iters, int32_t random_operands, float* sink, size_t sink_bytes, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,6 +29,7 @@ EXPORTS = [
     "tr_chunk_prefill_attn_workspace_size", "tr_chunk_prefill_attn",
     "tr_sequence_plan", "tr_sequence_prefill_attn_workspace_size", "tr_sequence_prefill_attn",
     "tr_linear_workspace_size", "tr_linear", "tr_set_tuning",
+    "tr_probe_mfma_loop_sink_bytes", "tr_probe_mfma_loop",
 ]
 
 
@@ -62,7 +63,8 @@ def lib():
         for name in ("tr_prefill_attn_workspace_size", "tr_prefill_attn_batched_workspace_size",
                      "tr_prefill_attn_gather_workspace_size", "tr_decode_attn_workspace_size",
                      "tr_chunk_prefill_attn_workspace_size", "tr_sequence_prefill_attn_workspace_size",
-                     "tr_linear_workspace_size", "tr_prefill_attn_static_scratch_bytes"):
+                     "tr_linear_workspace_size", "tr_prefill_attn_static_scratch_bytes",
+                     "tr_probe_mfma_loop_sink_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -218,6 +220,18 @@ def tr_prefill_attn_static(shape, q, k, v, q_pos, kv_len, out, stream=None):
 
 def tr_set_tuning(name, value):
     _check(lib().tr_set_tuning(name.encode(), C.c_int32(int(value))))
+
+
+def tr_probe_mfma_loop_sink_bytes():
+    return int(lib().tr_probe_mfma_loop_sink_bytes())
+
+
+def tr_probe_mfma_loop(iters, random_operands, sink, stream=None):
+    """Launch the matrix-instruction loop; returns the flops of the launch (the caller times it)."""
+    flops = C.c_double(0.0)
+    _check(lib().tr_probe_mfma_loop(C.c_int32(int(iters)), C.c_int32(1 if random_operands else 0), _dev(sink),
+                                    C.c_size_t(sink.numel() * sink.element_size()), C.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def tr_prefill_attn_batched_workspace_size(shape, cu_q, cache_row_start):

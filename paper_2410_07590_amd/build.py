@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libturborag_hip.so")
-SOURCES = ["tr_api.hip", "tr_copy.hip", "tr_attn.hip", "tr_attn_f32.hip", "tr_linear.hip"]
+SOURCES = ["tr_api.hip", "tr_copy.hip", "tr_attn.hip", "tr_attn_f32.hip", "tr_linear.hip", "tr_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept off for every HIP translation unit

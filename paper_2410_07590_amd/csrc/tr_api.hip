@@ -49,6 +49,20 @@ extern "C" int tr_set_tuning(const char* name, int32_t value)
     return tr_fail(TR_ERR_INVALID_ARG, "tr_set_tuning: unknown name '%s'", name);
 }
 
+extern "C" int tr_probe_mfma_loop(int32_t iters, int32_t random_operands, float* sink, size_t sink_bytes, double* flops, void* stream)
+{
+    tr_clear_error();
+    if (!sink || !flops) return tr_fail(TR_ERR_INVALID_ARG, "tr_probe_mfma_loop: sink or flops is NULL");
+    if (iters < 1 || iters > (1 << 24)) return tr_fail(TR_ERR_INVALID_ARG, "tr_probe_mfma_loop: iters %d outside [1, 2^24]", iters);
+    if (sink_bytes < tr_probe_mfma_loop_sink_bytes())
+        return tr_fail(TR_ERR_INVALID_ARG, "tr_probe_mfma_loop: sink holds %zu bytes, %zu needed", sink_bytes, tr_probe_mfma_loop_sink_bytes());
+    if (tr_launch_mfma_loop_probe(iters, random_operands != 0, sink, (hipStream_t)stream, flops) != 0)
+        return tr_fail(TR_ERR_HIP, "tr_probe_mfma_loop: launch failed: %s", hipGetErrorString(hipGetLastError()));
+    return TR_OK;
+}
+
+extern "C" size_t tr_probe_mfma_loop_sink_bytes(void) { return (size_t)TrChip::CUS * 512 * sizeof(float); }
+
 // No C++ exception may cross the C boundary: the entry points run inside these.
 template <class F> static int tr_guard_int(F&& f)
 {

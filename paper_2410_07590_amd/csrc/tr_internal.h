@@ -274,5 +274,7 @@ int tr_launch_blockdiag_attn_f32(const TrBlockDiagArgs& a, int head_dim, hipStre
 // counts; partial: fp32 [tr_linear_splits(M, N, K), M, N] when that count exceeds 1
 #define TR_LINEAR_MAX_OUT 4
 int tr_linear_splits(int32_t M, int32_t N, int32_t K);
+// sink: 256 * 512 floats.  *flops receives the multiply-add count x 2 of the launch.
+int tr_launch_mfma_loop_probe(int iters, int random_operands, float* sink, hipStream_t s, double* flops);
 int tr_launch_linear(const void* x, int32_t n_out, const void* const* w, void* const* y, const int32_t* n_features, void* partial,
                      int32_t M, int32_t K, hipStream_t s);
