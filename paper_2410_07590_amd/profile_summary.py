@@ -126,11 +126,12 @@ def counter_table(folder):
     return out
 
 
-def per_call(counts_by_kernel, trace_by_kernel, iters_hint=None):
-    """Launches of a kernel per bench call: its launch count relative to the least-launched kernel of the run."""
-    n = {k: v["n"] + 1 for k, v in trace_by_kernel.items()}
-    base = min(n.values()) if n else 1
-    return {k: max(1, round(v / base)) for k, v in n.items()}
+TRACE_ITERS, PMC_ITERS = 12, 5   # the --iters of the runs listed above
+
+
+def per_call(launches, iters):
+    """Launches of a kernel per library call; 0 for a kernel that only the set-up of the case launched."""
+    return launches // iters
 
 
 def git_commit():
@@ -173,7 +174,8 @@ def main():
              "Each block is one run of `rocprofv3 --kernel-trace --stats --output-format csv -d <dir>/<case>.trace -o out -- "
              "python3 bench.py --case <case> --iters 12` (from /tmp, TMPDIR=/tmp), summarised by "
              "`python -m paper_2410_07590_amd.profile_summary <dir>`; the first launch of each kernel is dropped.  "
-             "us = End_Timestamp - Start_Timestamp of the dispatch; `call us` = sum over the kernels of one library call.\n"]
+             "us = End_Timestamp - Start_Timestamp of the dispatch; `call us` = sum over the kernels of one library call; a kernel "
+             "marked set-up was launched by the preparation of the case only (it fills the cache the timed kernel reads).\n"]
     traces = {}
     for case in sorted(runs):
         if "trace" not in runs[case]:
@@ -182,15 +184,15 @@ def main():
         if not t:
             continue
         traces[case] = t
-        mult = per_call(None, t)
+        mult = {name: per_call(d["n"] + 1, TRACE_ITERS) for name, d in t.items()}
         lines.append("\n## %s\n" % case)
-        lines.append("| kernel | launches | per call | avg us | min us | max us | workgroups x threads | VGPR+AGPR | LDS bytes | scratch |")
+        lines.append("| kernel | launches | per call | avg us | min us | max us | workgroups x threads | VGPR+AGPR | static LDS | scratch |")
         lines.append("|---|---|---|---|---|---|---|---|---|---|")
         total = 0.0
         for name, d in t.items():
             total += d["avg"] * mult[name]
-            lines.append("| %s | %d | %d | %.2f | %.2f | %.2f | %s x %s | %s+%s | %s | %s |" % (
-                name, d["n"], mult[name], d["avg"], d["min"], d["max"], d["grid"], d["wg"], d["vgpr"], d["agpr"], d["lds"], d["scratch"]))
+            lines.append("| %s | %d | %s | %.2f | %.2f | %.2f | %s x %s | %s+%s | %s | %s |" % (
+                name, d["n"], mult[name] or "set-up", d["avg"], d["min"], d["max"], d["grid"], d["wg"], d["vgpr"], d["agpr"], d["lds"], d["scratch"]))
         lines.append("\ncall us (sum of avg x launches per call): %.2f" % total)
     write(args.out, "kernel_trace_by_workload.md", lines)
 
@@ -221,12 +223,13 @@ def main():
         if case == "copy" or "fetch" not in runs[case] or "write" not in runs[case] or ff is None or wf is None:
             continue
         fe, wr = counter_table(runs[case]["fetch"]), counter_table(runs[case]["write"])
-        base = min(v["_launches"] + 1 for v in fe.values()) if fe else 1
         sums = collections.defaultdict(float)
         for name in fe:
             if name not in wr or not ours(name):
                 continue
-            mult = max(1, round((fe[name]["_launches"] + 1) / base))
+            mult = per_call(fe[name]["_launches"] + 1, PMC_ITERS)
+            if mult == 0:
+                continue   # launched by the set-up of the case only
             f_k, w_k = fe[name].get("FETCH_SIZE", 0.0), wr[name].get("WRITE_SIZE", 0.0)
             rd, wt = f_k * ff / 1024, w_k * wf / 1024
             lines.append("| %s | %s | %d | %.1f | %.1f | %.2f | %.2f | %.2f |" % (case, name, mult, f_k, w_k, rd, wt, rd + wt))
