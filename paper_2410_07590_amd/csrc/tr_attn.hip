@@ -391,8 +391,28 @@ __device__ __forceinline__ void issue_prologue(const __bf16* __restrict__ k, con
             issue_tile<D, NW, KT, AUX>(k, v, w.row_elems, w.head_off, w.kt_begin + p * KT, w.key_clamp, smem + p * Geo<D>::STAGE_BYTES, wave, lane);
 }
 
+// This wave's loads of one whole tile whose 64 rows all exist (no clamping): the lane's byte offsets inside the tile
+// were computed once (dk, dv), the tile's first row is a uniform base, so a load costs no vector arithmetic.
+template <int D, int NW, int AUX>
+__device__ __forceinline__ void issue_tile_at(const char* __restrict__ ktile, const char* __restrict__ vtile,
+                                              const uint32_t (&dk)[Geo<D>::NI / NW], const uint32_t (&dv)[Geo<D>::NI / NW],
+                                              uint32_t lds_wave /* LDS address of this wave's first 1 KB slot in stage 0 (uniform) */,
+                                              int stage_off /* constant */)
+{
+    using G = Geo<D>;
+#pragma unroll
+    for (int ii = 0; ii < G::NI / NW; ++ii) {
+        const uint32_t dst = lds_wave + (uint32_t)(stage_off + NW * ii * 1024);
+        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(ktile + dk[ii]), (LDS_AS void*)(uintptr_t)dst, 16, 0, AUX);
+        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(vtile + dv[ii]), (LDS_AS void*)(uintptr_t)(dst + G::TILE_BYTES), 16, 0, AUX);
+    }
+}
+
 // The tile loop shared by both kernels (issue_prologue has run).  Tile [kt, kt+64) needs per-element masking iff
-// kt+63 > mask_hi_min or kt < mask_lo_max.
+// kt+63 > mask_hi_min or kt < mask_lo_max.  The loop is unrolled over the ring so that the stage of every LDS
+// access is a constant of the instruction: the operand reads then need no address arithmetic at all (the lane's
+// offsets inside a stage are loop constants, the stage goes into the instruction's offset field, whose 16 bits
+// reach two 32 KB stages: a four-stage ring keeps a second set of offsets for stages 2 and 3).
 template <int D, int NW, int NS, int AUX = 0>
 __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const __bf16* __restrict__ v, const Walk& w,
                                            const RowCtx& rc, const bf16x8 (&qf)[D / 16], int mask_hi_min, int mask_lo_max,
@@ -401,6 +421,8 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
     using G = Geo<D>;
     constexpr int IPW = 2 * G::NI / NW; // loads each wave issues per tile
     static_assert(G::NI % NW == 0, "tile loads must divide evenly over the waves");
+    static_assert(NS == 2 || NS == 4, "the ring has two or four stages");
+    constexpr int BANKS = NS / 2;        // sets of lane offsets: one per 64 KB of ring
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int i16 = lane & 15, colhalf = (lane >> 4) & 1;
@@ -408,37 +430,67 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
     const int wave_hi_max = wave_max_i(rc.valid ? rc.key_hi : INT32_MIN);
     const int wave_lo_min = wave_min_i(rc.valid ? rc.key_lo : INT32_MAX);
 
-    // LDS byte offsets of this lane's operands inside a stage
-    int koff[D / 16];
+    // LDS addresses of this lane's operands in stage 2b (bank b serves stages 2b and 2b + 1): whole addresses, the
+    // ring's base included, so that what an access adds is a constant that fits its offset field
+    const int lds0 = (int)(uintptr_t)smem;
+    const uint32_t lds_wave = (uint32_t)__builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
+    int koff[BANKS][D / 16];
+    int voff[BANKS][D / 32];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) koff[ks] = c * D * 2 + (((2 * ks + h) ^ G::kswz(c)) * 16);
-    int voff[D / 32];
-    {
+    for (int b = 0; b < BANKS; ++b) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) koff[b][ks] = lds0 + b * 2 * G::STAGE_BYTES + c * D * 2 + (((2 * ks + h) ^ G::kswz(c)) * 16);
         const int r = 4 * h + (i16 >> 2); // row inside an 8-row k-slot block; rows 8 apart share the swizzle
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
-            voff[db] = r * D * 2 + (4 * (db ^ G::vswz(r)) + 2 * colhalf + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
+            voff[b][db] = lds0 + b * 2 * G::STAGE_BYTES + r * D * 2 + (4 * (db ^ G::vswz(r)) + 2 * colhalf + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
     }
+    // byte offsets of this wave's tile loads from the tile's first row
+    uint32_t dk[G::NI / NW], dv[G::NI / NW];
+    {
+        const int r_in = lane / G::CPR, pc = lane % G::CPR;
+        const uint32_t row_bytes = (uint32_t)w.row_elems * 2u;
+#pragma unroll
+        for (int ii = 0; ii < G::NI / NW; ++ii) {
+            const int row = (wave + NW * ii) * G::RPI + r_in;
+            const int ck = pc ^ G::kswz(row);
+            const int cv = 4 * ((pc >> 2) ^ G::vswz(row)) + (pc & 3);
+            dk[ii] = (uint32_t)row * row_bytes + (uint32_t)(w.head_off + ck * 8) * 2u;
+            dv[ii] = (uint32_t)row * row_bytes + (uint32_t)(w.head_off + cv * 8) * 2u;
+        }
+    }
+    const int64_t row_bytes64 = w.row_elems * 2;
 
     const int n_tiles = w.n_tiles;
     bf16x8 bpk[2][2];
-    for (int t = 0; t < n_tiles; ++t) {
-        const int kt = w.kt_begin + t * KT;
-        // tile t has landed once at most the loads of the tiles issued after it are outstanding
-        const int later = min(NS - 2, n_tiles - 1 - t);
-        if (NS >= 4 && later >= 2) wait_vm<2 * IPW>();
-        else if (NS >= 3 && later >= 1) wait_vm<IPW>();
-        else wait_vm<0>();
-        __builtin_amdgcn_s_barrier(); // every wave's share of tile t is in LDS; everyone is done with tile t-1
-        if (t + NS - 1 < n_tiles)
-            issue_tile<D, NW, KT, AUX>(k, v, w.row_elems, w.head_off, kt + (NS - 1) * KT, w.key_clamp,
-                              smem + ((t + NS - 1) % NS) * G::STAGE_BYTES, wave, lane);
-        const bool active = (kt <= wave_hi_max) && (kt + KT - 1 >= wave_lo_min); // wave-uniform
-        if (active) {
-            LDS_AS const char* stage = smem + (t % NS) * G::STAGE_BYTES;
-            const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
-            scores_softmax<D, 2>(stage, qf, rc, kt, need_mask, koff, h, acc, bpk);
-            weighted_values<D, 2>(stage + G::TILE_BYTES, bpk, voff, acc);
+    for (int t0 = 0; t0 < n_tiles; t0 += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int t = t0 + s;
+            if (t >= n_tiles) break;
+            const int kt = w.kt_begin + t * KT;
+            // tile t has landed once at most the loads of the tiles issued after it are outstanding
+            const int later = min(NS - 2, n_tiles - 1 - t);
+            if (NS >= 4 && later >= 2) wait_vm<2 * IPW>();
+            else if (NS >= 3 && later >= 1) wait_vm<IPW>();
+            else wait_vm<0>();
+            __builtin_amdgcn_s_barrier(); // every wave's share of tile t is in LDS; everyone is done with tile t-1
+            if (t + NS - 1 < n_tiles) {
+                const int ktn = kt + (NS - 1) * KT;
+                const int dst_off = ((s + NS - 1) % NS) * G::STAGE_BYTES; // a constant once the loop is unrolled
+                if (ktn + KT - 1 <= w.key_clamp)
+                    issue_tile_at<D, NW, AUX>((const char*)k + (int64_t)ktn * row_bytes64, (const char*)v + (int64_t)ktn * row_bytes64, dk, dv, lds_wave, dst_off);
+                else
+                    issue_tile<D, NW, KT, AUX>(k, v, w.row_elems, w.head_off, ktn, w.key_clamp, smem + dst_off, wave, lane);
+            }
+            const bool active = (kt <= wave_hi_max) && (kt + KT - 1 >= wave_lo_min); // wave-uniform
+            if (active) {
+                // stages 2b and 2b + 1 are addressed from bank b's offsets; the rest is a constant of the instruction
+                LDS_AS const char* stage = (LDS_AS const char*)(uintptr_t)((s % 2) * G::STAGE_BYTES);
+                const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
+                scores_softmax<D, 2>(stage, qf, rc, kt, need_mask, koff[s / 2], h, acc, bpk);
+                weighted_values<D, 2>(stage + G::TILE_BYTES, bpk, voff[s / 2], acc);
+            }
         }
     }
 }
