@@ -78,6 +78,23 @@ __device__ __forceinline__ int xcd_remap(int bid, int n)
     return x * q + (x < r ? x : r) + idx;
 }
 
+// Maximum and sum over the two lanes c and c + 32, which hold the two key halves of one query column, through the
+// cross-half swap of the vector unit.  These exchanges sit on the critical path of every tile: an LDS permute would put
+// an LDS round trip there, and its wait would also wait for every operand read in flight.
+// permlane32_swap(u, u): result[0] = lanes 0..31 of u in both halves, result[1] = lanes 32..63 of u in both halves.
+__device__ __forceinline__ float column_max(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float column_sum(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __device__ __forceinline__ int wave_max_i(int v)
 {
 #pragma unroll
@@ -250,9 +267,16 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ k, const _
 
 // One tile of 32 KB keys in two phases.  Phase A: S^T = K Q^T and the online softmax, leaving P^T packed as bf16 B
 // operands.  Phase B: O^T += V^T P^T.  krows / vrows point at the tile's first K / V row in LDS, kt is its first key.
-template <int D, int KB>
+struct NoHook {
+    __device__ __forceinline__ void operator()(int) const {}
+};
+
+// between(ks) runs after the products of k-step ks have been issued: the tile loop puts its loads of a later tile
+// there, so that their issue falls into the shadow of the matrix instructions instead of in front of them.
+template <int D, int KB, class Between = NoHook>
 __device__ __forceinline__ void scores_softmax(LDS_AS const char* krows, const bf16x8 (&qf)[D / 16], const RowCtx& rc, int kt,
-                                               bool need_mask, const int (&koff)[D / 16], int h, Acc<D>& acc, bf16x8 (&bpk)[KB][2])
+                                               bool need_mask, const int (&koff)[D / 16], int h, Acc<D>& acc, bf16x8 (&bpk)[KB][2],
+                                               Between between = Between())
 {
     // scores relative to the row reference, in the log2 domain (the queries carry log2(e)/sqrt(d)): the
     // accumulators start at -mref, so P = exp2(S) needs no further arithmetic
@@ -277,6 +301,7 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* krows, const b
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) a[ks % PD][kb] = *(LDS_AS const bf16x8*)(krows + koff[ks + PD] + kb * 32 * D * 2);
         }
+        between(ks);
         __builtin_amdgcn_sched_barrier(0);
     }
     // accumulator element e of block kb is key kt + 32 kb + 8 (e >> 2) + 4 h + (e & 3), query column c
@@ -294,12 +319,12 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* krows, const b
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32)); // both half-waves hold keys of the same query column
+    mx = column_max(mx); // both half-waves hold keys of the same query column
     // lazy reference update (exact: any reference gives the same softmax).  `first`: nothing accumulated yet and the
     // tile sits far below the reference - move the reference down so that exp2 does not underflow.  Lanes c and c + 32
     // hold the two key halves of ONE query column and share its reference, so the decision is taken on the column's
     // denominator: a row whose first visible keys all fell into one half must not move the other half's reference alone.
-    const float l_col = acc.l + __shfl_xor(acc.l, 32);
+    const float l_col = column_sum(acc.l);
     const bool first = (l_col == 0.0f) && (mx < REREF_BELOW) && (mx > -INFINITY);
     const bool grow = (mx > RESCALE_SLACK) || first;
     if (__any(grow)) { // rare
@@ -393,6 +418,16 @@ __device__ __forceinline__ void issue_prologue(const __bf16* __restrict__ k, con
 
 // This wave's loads of one whole tile whose 64 rows all exist (no clamping): the lane's byte offsets inside the tile
 // were computed once (dk, dv), the tile's first row is a uniform base, so a load costs no vector arithmetic.
+// load pair ii of this wave: 1 KB of the K tile and 1 KB of the V tile
+template <int D, int NW, int AUX>
+__device__ __forceinline__ void issue_pair_at(const char* __restrict__ ktile, const char* __restrict__ vtile, uint32_t dk, uint32_t dv,
+                                              uint32_t lds_wave, int stage_off, int ii)
+{
+    const uint32_t dst = lds_wave + (uint32_t)(stage_off + NW * ii * 1024);
+    __builtin_amdgcn_global_load_lds((const GLB_AS void*)(ktile + dk), (LDS_AS void*)(uintptr_t)dst, 16, 0, AUX);
+    __builtin_amdgcn_global_load_lds((const GLB_AS void*)(vtile + dv), (LDS_AS void*)(uintptr_t)(dst + Geo<D>::TILE_BYTES), 16, 0, AUX);
+}
+
 template <int D, int NW, int AUX>
 __device__ __forceinline__ void issue_tile_at(const char* __restrict__ ktile, const char* __restrict__ vtile,
                                               const uint32_t (&dk)[Geo<D>::NI / NW], const uint32_t (&dv)[Geo<D>::NI / NW],
@@ -401,11 +436,7 @@ __device__ __forceinline__ void issue_tile_at(const char* __restrict__ ktile, co
 {
     using G = Geo<D>;
 #pragma unroll
-    for (int ii = 0; ii < G::NI / NW; ++ii) {
-        const uint32_t dst = lds_wave + (uint32_t)(stage_off + NW * ii * 1024);
-        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(ktile + dk[ii]), (LDS_AS void*)(uintptr_t)dst, 16, 0, AUX);
-        __builtin_amdgcn_global_load_lds((const GLB_AS void*)(vtile + dv[ii]), (LDS_AS void*)(uintptr_t)(dst + G::TILE_BYTES), 16, 0, AUX);
-    }
+    for (int ii = 0; ii < G::NI / NW; ++ii) issue_pair_at<D, NW, AUX>(ktile, vtile, dk[ii], dv[ii], lds_wave, stage_off, ii);
 }
 
 // The tile loop shared by both kernels (issue_prologue has run).  Tile [kt, kt+64) needs per-element masking iff
@@ -475,20 +506,29 @@ __device__ __forceinline__ void attn_tiles(const __bf16* __restrict__ k, const _
             else if (NS >= 3 && later >= 1) wait_vm<IPW>();
             else wait_vm<0>();
             __builtin_amdgcn_s_barrier(); // every wave's share of tile t is in LDS; everyone is done with tile t-1
-            if (t + NS - 1 < n_tiles) {
-                const int ktn = kt + (NS - 1) * KT;
-                const int dst_off = ((s + NS - 1) % NS) * G::STAGE_BYTES; // a constant once the loop is unrolled
-                if (ktn + KT - 1 <= w.key_clamp)
-                    issue_tile_at<D, NW, AUX>((const char*)k + (int64_t)ktn * row_bytes64, (const char*)v + (int64_t)ktn * row_bytes64, dk, dv, lds_wave, dst_off);
-                else
-                    issue_tile<D, NW, KT, AUX>(k, v, w.row_elems, w.head_off, ktn, w.key_clamp, smem + dst_off, wave, lane);
-            }
             const bool active = (kt <= wave_hi_max) && (kt + KT - 1 >= wave_lo_min); // wave-uniform
+            const int ktn = kt + (NS - 1) * KT;
+            const int dst_off = ((s + NS - 1) % NS) * G::STAGE_BYTES; // a constant once the loop is unrolled
+            const bool more = t + NS - 1 < n_tiles;
+            const bool whole = ktn + KT - 1 <= w.key_clamp;
+            const char* ktile = (const char*)k + (int64_t)ktn * row_bytes64;
+            const char* vtile = (const char*)v + (int64_t)ktn * row_bytes64;
+            // the loads of tile t + NS - 1: a wave that computes this tile issues them between its first score products
+            // (below); a wave that skips the tile, or a tile with clamped rows, issues them here
+            // (measured: the four-wave kernels, whose waves issue twice as many loads per tile, gain 2-5 %; the
+            // eight-wave kernel loses the 2 % the unrolled ring gave it, so it keeps its loads in front)
+            const bool defer = (NW == 4) && more && whole && active;
+            if (more && !defer) {
+                if (whole) issue_tile_at<D, NW, AUX>(ktile, vtile, dk, dv, lds_wave, dst_off);
+                else issue_tile<D, NW, KT, AUX>(k, v, w.row_elems, w.head_off, ktn, w.key_clamp, smem + dst_off, wave, lane);
+            }
             if (active) {
                 // stages 2b and 2b + 1 are addressed from bank b's offsets; the rest is a constant of the instruction
                 LDS_AS const char* stage = (LDS_AS const char*)(uintptr_t)((s % 2) * G::STAGE_BYTES);
                 const bool need_mask = (kt + KT - 1 > mask_hi_min) || (kt < mask_lo_max);
-                scores_softmax<D, 2>(stage, qf, rc, kt, need_mask, koff[s / 2], h, acc, bpk);
+                scores_softmax<D, 2>(stage, qf, rc, kt, need_mask, koff[s / 2], h, acc, bpk, [&](int ks) {
+                    if (ks < G::NI / NW && defer) issue_pair_at<D, NW, AUX>(ktile, vtile, dk[ks], dv[ks], lds_wave, dst_off, ks);
+                });
                 weighted_values<D, 2>(stage + G::TILE_BYTES, bpk, voff[s / 2], acc);
             }
         }
