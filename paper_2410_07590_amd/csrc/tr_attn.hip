@@ -314,11 +314,12 @@ __device__ __forceinline__ void scores_softmax(LDS_AS const char* krows, const b
                 if (key < rc.key_lo || key > rc.key_hi) s[kb][e] = -INFINITY;
             }
     }
-    float mx = -INFINITY;
+    float part[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}; // four short chains instead of one long one
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
+        for (int e = 0; e < 16; ++e) part[e & 3] = fmaxf(part[e & 3], s[kb][e]);
+    float mx = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
     mx = column_max(mx); // both half-waves hold keys of the same query column
     // lazy reference update (exact: any reference gives the same softmax).  `first`: nothing accumulated yet and the
     // tile sits far below the reference - move the reference down so that exp2 does not underflow.  Lanes c and c + 32
