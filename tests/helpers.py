@@ -22,6 +22,12 @@ def bits(t):
     return synth.as_oracle_array(t)
 
 
+def bits_t(t):
+    """The tensor's storage as integers, for bit-for-bit comparisons that treat equal NaNs as equal."""
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.int16 if t.element_size() == 2 else torch.int32)
+
+
 def assert_same_bits(got, want, what, max_mismatch_frac=0.0):
     """Bit-for-bit equality of two storage-typed arrays.  For rotated keys a tiny fraction of one-ulp
     differences is tolerated: device and host sin/cos are each within ~1 ulp of fp64, so an fp64

@@ -381,6 +381,31 @@ def tuning(B):
         B.tr_set_tuning(n, 0)
 
 
+HALF = 1   # rope_layout: pair m = channels (m, m + head_dim / 2)
+
+EIGHT_WAVE_SHAPES = [synth.LLAMA3_8B, replace(synth.LLAMA3_8B, rope_layout=HALF), synth.Shape(14, 2, 64, "bf16", 1.0e6),
+                     synth.Shape(16, 2, 64, "bf16", 1.0e4, HALF)]
+
+
+@pytest.mark.parametrize("shape_idx", range(len(EIGHT_WAVE_SHAPES)))
+@pytest.mark.parametrize("split", [0, 1])
+def test_eight_wave_kernel_ring_and_ragged_tail(B, tuning, shape_idx, split):
+    """The 256-row workgroup (four-stage ring, both sets of LDS offsets) on each head_dim and channel pairing: 14 key
+    tiles, so the ring wraps three times, a last tile with missing rows (the clamped loads), query tokens that end
+    inside a row tile; once as one key range per row tile and once cut into splits."""
+    sh = EIGHT_WAVE_SHAPES[shape_idx]
+    tuning("wg_rows", 256)
+    if not split:
+        tuning("target_items", 1)
+    cfg = synth.scaled(synth.CONFIGS[2], shape=sh, store_chunks=6, chunk_len_lo=130, chunk_len_hi=157, chunks_per_request=6, n_q_lo=75, n_q_hi=75)
+    store = synth.make_store(cfg)
+    sd = _store_dev(B, sh, store)
+    req = synth.make_requests(cfg, store)[0]
+    assert (req.n_doc + req.n_q) % 64 != 0 and req.n_doc + req.n_q > 13 * 64
+    err, n_bad = H.check_request(B, sh, store, sd, req)
+    print("eight-wave kernel %s split=%d: max abs err %.3e" % (sh, split, err))
+
+
 def test_short_query_kernel_with_causal_rows(B, tuning):
     """The key-splitting kernel forced onto queries of up to 40 tokens: several row tiles, causal mask among them."""
     tuning("wg_rows", 32)
@@ -620,7 +645,6 @@ def test_sequence_form_reproduces_the_offline_chunk_prefill(B):
 
 
 # ---- the half-split RoPE layout: pair m = channels (m, m + head_dim/2) -----------------------------------------------
-HALF = 1
 
 
 @pytest.mark.parametrize("case", range(len(RAGGED)))
