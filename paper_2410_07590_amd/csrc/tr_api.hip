@@ -8,6 +8,7 @@
 #include <string.h>
 #include <algorithm>
 #include <functional>
+#include <mutex>
 #include <new>
 
 // ---- errors ---------------------------------------------------------------------------------------------------
@@ -534,6 +535,35 @@ double launch_makespan(const std::vector<int>& item_tiles, int slots_per_xcd)
     return worst;
 }
 
+// The key cuts the launch search chose for the last few batch shapes (host memory only; any thread).
+struct CutCacheEntry {
+    std::vector<int64_t> key;
+    std::vector<SplitPlan> cut;
+};
+constexpr int CUT_CACHE_ENTRIES = 8;
+std::mutex g_cut_mu;
+CutCacheEntry g_cut_cache[CUT_CACHE_ENTRIES];
+unsigned g_cut_next = 0;
+
+bool cut_cache_lookup(const std::vector<int64_t>& key, std::vector<SplitPlan>* cut)
+{
+    std::lock_guard<std::mutex> lock(g_cut_mu);
+    for (const CutCacheEntry& e : g_cut_cache)
+        if (e.key == key) {
+            *cut = e.cut;
+            return true;
+        }
+    return false;
+}
+
+void cut_cache_store(const std::vector<int64_t>& key, const std::vector<SplitPlan>& cut)
+{
+    std::lock_guard<std::mutex> lock(g_cut_mu);
+    CutCacheEntry& e = g_cut_cache[g_cut_next++ % CUT_CACHE_ENTRIES];
+    e.key = key;
+    e.cut = cut;
+}
+
 // Fills the per-request descriptors of one launch (requests [r0, r1)); returns the partial rows it needs.
 int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t r0, size_t r1, TrPrefixArgs* a,
                     bool* any_split, int* total_tokens, int* wg_rows_out)
@@ -558,6 +588,20 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
     // cut into pieces of about one common length, and that length is chosen by playing the launch through
     // (launch_makespan) for a range of candidates, with the traffic of the partial results priced in.
     if (want_split > 1 && r1 - r0 > 1 && wg_rows != 32 && tr_knob(TR_KNOB_TARGET_ITEMS, 0) == 0) {
+        // The search costs tens of microseconds of host time and a call runs it twice (workspace check, then the
+        // launch), after the caller's own workspace query: its result is kept for the last few batch shapes.  The
+        // key is everything the search reads: head counts, tile geometry, the split floor, and (n_q, kv_len) of every
+        // request in order.
+        std::vector<int64_t> key;
+        key.reserve(8 + 2 * (r1 - r0));
+        for (int64_t x : {(int64_t)sh->n_q_heads, (int64_t)sh->n_kv_heads, (int64_t)sh->head_dim, (int64_t)wg_rows, (int64_t)min_split_keys,
+                          (int64_t)key_tile})
+            key.push_back(x);
+        for (size_t r = r0; r < r1; ++r) {
+            key.push_back(reqs[r].n_q);
+            key.push_back(reqs[r].kv_len);
+        }
+        if (!cut_cache_lookup(key, &cut)) {
         double walked = 0.0; // keys walked by all row tiles of all KV heads
         for (size_t r = r0; r < r1; ++r) walked += (double)((reqs[r].n_q + tpt - 1) / tpt) * sh->n_kv_heads * (double)reqs[r].kv_len;
         const int slots_per_xcd = (wg_rows == 256 ? TrChip::SLOTS_256 : TrChip::SLOTS_128) / TrChip::XCDS;
@@ -589,6 +633,8 @@ int64_t plan_prefix(const tr_shape* sh, const std::vector<ReqGeom>& reqs, size_t
             }
             const double cost = launch_makespan(item_tiles, slots_per_xcd) * STEP_US + 2.0 * partial_bytes / PARTIAL_BYTES_PER_US;
             if (cost < best) { best = cost; cut = cand; }
+        }
+        cut_cache_store(key, cut);
         }
     }
     int items = 0, n = 0, toks = 0;

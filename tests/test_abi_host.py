@@ -470,6 +470,32 @@ def test_linear_validation(L):
     assert L.tr_linear_workspace_size(C.c_int32(64), C.c_int32(1), bad_p, C.c_int32(3584)) == 0   # invalid shape: 0
 
 
+def test_batched_plan_is_the_same_with_and_without_its_memo(L):
+    """The launch search of a mixed batch keeps its result for the last few batch shapes.  Twelve shapes (more than it
+    keeps) queried forwards, backwards and forwards again, and once more after a policy override and its removal, give
+    the same workspace sizes every time; two batches that differ in one cache length only are told apart."""
+    rng = np.random.Generator(np.random.PCG64(99))
+    sh = B.make_shape(28, 4, 128, "bf16", 1.0e6)
+    batches = []
+    for _ in range(12):
+        n_req = int(rng.integers(2, 20))
+        n_q = rng.integers(1, 129, n_req)
+        n_doc = rng.integers(2000, 12000, n_req)
+        batches.append((np.concatenate([[0], np.cumsum(n_q)]).astype(np.int32), np.concatenate([[0], np.cumsum(n_doc + n_q)]).astype(np.int64)))
+    size = lambda b: B.tr_prefill_attn_batched_workspace_size(sh, b[0], b[1])
+    first = [size(b) for b in batches]
+    assert [size(b) for b in reversed(batches)] == first[::-1]
+    assert [size(b) for b in batches] == first
+    B.tr_set_tuning("min_split_keys", 1024)
+    [size(b) for b in batches]   # whatever the override chooses must not stick once it is removed
+    B.tr_set_tuning("min_split_keys", 0)
+    assert [size(b) for b in batches] == first
+    cu_q, crs = batches[0]
+    longer = crs.copy()
+    longer[-1] += 4096
+    assert size((cu_q, longer)) >= first[0] and size(batches[0]) == first[0]
+
+
 def test_launch_planners_on_random_request_mixes(L):
     """The host-side launch planners (key splits per request, chosen by playing the launch through) on 300 seeded
     random request mixes, through the workspace-size entry points: they return, the same input gives the same size,
