@@ -176,6 +176,17 @@ def main():
         ceil.update(measured_mfma_loop(torch, B))
         result["measured_ceilings"] = ceil
         result["hbm_copy_ceiling_gbs"] = ceil["hbm_copy_gbs"]
+        notes = {"batched-serving-16req": "one batch replayed: 390 MB of caches, more than the 256 MB last-level cache holds",
+                 "offline-64x512": "cold by size: 840 MB of q, k, v, k' and out per call",
+                 "32x1024-chunks-plus-256-query-llama3-8b": "cold by size: 850 MB per call",
+                 "decode-%dx%d-qwen2-7b" % (DECODE_BATCH, DECODE_KV): "cold by size: 537 MB of cache rows per call",
+                 "short-query-16-tokens-over-12288-rows-qwen2-7b": "cold: twelve caches of 25 MB in turn",
+                 "short-query-16req-x-16-tokens-over-12288-rows-qwen2-7b": "cold: two sets of caches of 403 MB in turn",
+                 "qwen2-7b-qkv-projection-64-tokens": "cold: the weights of ten layers in turn (587 MB)",
+                 "qwen2-7b-output-projection-64-tokens": "cold: the weights of ten layers in turn (587 MB)"}
+        for r in roof_extra:
+            if "memory" not in r and r.get("workload") in notes:
+                r["memory"] = notes[r["workload"]]
         for r in [result["roofline"]] + roof_extra:   # the same fractions against what the chip delivered in this run
             if r.get("bound") == "mfma":
                 r["frac_of_measured_loop"] = round(r["achieved"] / ceil["mfma_loop_tflops_random_operands"], 4)
@@ -303,6 +314,9 @@ def bench_step(torch, B, synth, acct, cfg, n_variants, steps, warmup, eager_only
                   {"kernel": "tr_kv_append", "workload": cfg.name, "avg_us": round(t_app[0], 2), "median_us": round(t_app[1], 2)}]
     if t_raw:
         roof_extra.append(hbm_roof("tr_kv_assemble_raw", cfg.name, asm_bytes, t_raw))
+    touched = (2 * store.k.numel() * store.k.element_size() * 2 + sum(2 * v["cache_k"].numel() * v["cache_k"].element_size() for v in variants)) // 1000000
+    for r in [roofline] + roof_extra:
+        r["memory"] = "cold: %d request variants in turn, %d MB of store copies and caches per cycle (last-level cache: 256 MB)" % (n_variants, touched)
     kernel_us = {"assemble_append": round(t_asa[0], 2), "prefill_attn": round(t_att[0], 2),
                  "assemble_alone": round(t_asm[0], 2), "append_alone": round(t_app[0], 2)}
     return {"graph_us": graph_us, "eager_us": eager_us, "kernel_us": kernel_us, "roofline": roofline, "roof_extra": roof_extra}
