@@ -95,18 +95,24 @@ __device__ __forceinline__ float column_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-__device__ __forceinline__ int wave_max_i(int v)
+// Maximum / minimum of an int over the wave, as a uniform value.  Four cross-lane steps inside each row of 16 lanes on
+// the vector unit's data-parallel path (pairs, quads, the mirrored half-row, the mirrored row: max and min do not care
+// which lanes meet, only that all do), then the four rows' results through scalar registers.  Every lane of the wave must
+// be active.  (A butterfly of six LDS permutes does the same with six dependent LDS round trips; a workgroup of the
+// offline kernel needs four such reductions before its first tile load can go out.)
+template <bool MAX> __device__ __forceinline__ int wave_reduce_i(int v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o));
-    return __builtin_amdgcn_readfirstlane(v);
+    auto op = [](int a, int b) { return MAX ? max(a, b) : min(a, b); };
+    v = op(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false));  // quad_perm [1,0,3,2]
+    v = op(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false));  // quad_perm [2,3,0,1]
+    v = op(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false)); // row_half_mirror
+    v = op(v, __builtin_amdgcn_update_dpp(v, v, 0x140, 0xf, 0xf, false)); // row_mirror
+    const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+    const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+    return op(op(r0, r1), op(r2, r3));
 }
-__device__ __forceinline__ int wave_min_i(int v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = min(v, __shfl_xor(v, o));
-    return __builtin_amdgcn_readfirstlane(v);
-}
+__device__ __forceinline__ int wave_max_i(int v) { return wave_reduce_i<true>(v); }
+__device__ __forceinline__ int wave_min_i(int v) { return wave_reduce_i<false>(v); }
 
 // ---- rotated queries (Eq. 3 at the token's position id) -------------------------------------------------------
 // Lane (c = lane & 31, h = lane >> 5) ends up holding Q'[row c][16 ks + 8 h .. +7] for ks < D/16, scaled by
