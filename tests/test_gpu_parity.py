@@ -406,6 +406,30 @@ def test_eight_wave_kernel_ring_and_ragged_tail(B, tuning, shape_idx, split):
     print("eight-wave kernel %s split=%d: max abs err %.3e" % (sh, split, err))
 
 
+def test_eight_wave_kernel_interior_loop_boundaries(B, tuning):
+    """The eight-wave kernel walks ring-fulls of four interior tiles in a loop of its own and hands over to the general
+    loop: document lengths that put the hand-over at every position relative to the ring (7 to 13 tiles and a few keys
+    either side of a tile edge), one key range per row tile, 20 query tokens so that the causal edge sits in the last
+    tile or two."""
+    sh = synth.LLAMA3_8B
+    tuning("wg_rows", 256)
+    tuning("target_items", 1)
+    worst = 0.0
+    for n_doc in (7 * 64 - 20, 8 * 64 - 21, 8 * 64 - 19, 9 * 64 - 20, 10 * 64 + 3, 11 * 64 - 20, 12 * 64 - 1, 12 * 64, 13 * 64 - 17):
+        lens = (n_doc // 3, n_doc // 3, n_doc - 2 * (n_doc // 3))
+        cfg = synth.scaled(synth.CONFIGS[2], shape=sh, store_chunks=3, chunk_len_lo=1, chunk_len_hi=1, chunks_per_request=3, n_q_lo=20, n_q_hi=20)
+        rng = synth.rng_for(cfg, n_doc)
+        row_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        store = synth.Store(synth.normal_tensor(rng, (n_doc, sh.n_kv_heads, sh.head_dim), sh.torch_dtype),
+                            synth.normal_tensor(rng, (n_doc, sh.n_kv_heads, sh.head_dim), sh.torch_dtype), row_start)
+        sd = _store_dev(B, sh, store)
+        req = synth.make_requests(cfg, store)[0]
+        assert req.n_doc == n_doc
+        err, _ = H.check_request(B, sh, store, sd, req)
+        worst = max(worst, err)
+    print("eight-wave kernel, hand-over positions: max abs err %.3e" % worst)
+
+
 def test_short_query_kernel_with_causal_rows(B, tuning):
     """The key-splitting kernel forced onto queries of up to 40 tokens: several row tiles, causal mask among them."""
     tuning("wg_rows", 32)
