@@ -343,6 +343,57 @@ __global__ __launch_bounds__(256) void append_kernel(const TrAppendArgs a)
                              (int64_t)a.desc[r].q_row0 + i, (int64_t)a.desc[r].dst_row0 + i, m);
 }
 
+// The same rows for launches of many tokens (a store of un-rotated keys assembled at the final position ids, the key
+// rotation of the one-pass sequence call): a thread owns one 16-byte unit of a token, computes the (cos, sin) of the
+// pairs that unit takes part in once, and walks the KV heads with 16-byte accesses, where the kernel above moves one
+// pair (4 bytes) per thread and head.  Same arithmetic, so the same bits.
+constexpr int APPEND_UNITS_HEADS = 8; // KV heads in flight per thread
+template <int DTYPE, bool HALF>
+__global__ __launch_bounds__(256) void append_units_kernel(const TrAppendArgs a)
+{
+    constexpr int P = Unit<DTYPE>::PAIRS, E = UnitHalf<DTYPE>::ELEMS;
+    constexpr int N_CS = HALF ? E : P; // pairs this thread's unit takes part in
+    const int head_units = a.head_dim * (DTYPE == TR_BF16 ? 2 : 4) / 16; // a power of two, at most 32: a token's units share a wave
+    const int hmask = head_units >> 1;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int tok = (int)(gid / head_units), unit = (int)(gid % head_units);
+    if (tok >= a.total_tokens) return; // whole tokens leave together, so the partner lane of the half-split layout stays
+    int r = 0, base = 0;
+    while (r + 1 < a.n_desc && tok >= base + a.desc[r].n_q) { base += a.desc[r].n_q; ++r; }
+    const int i = tok - base;
+    const int pos = a.q_pos ? a.q_pos[a.desc[r].q_row0 + i] : a.desc[r].pos0 + i;
+    const int64_t row_units = (int64_t)a.n_kv_heads * head_units;
+    const uint4* ks = (const uint4*)a.k_new + ((int64_t)a.desc[r].q_row0 + i) * row_units + unit;
+    const uint4* vs = (const uint4*)a.v_new + ((int64_t)a.desc[r].q_row0 + i) * row_units + unit;
+    uint4* kd = (uint4*)a.cache_k + ((int64_t)a.desc[r].dst_row0 + i) * row_units + unit;
+    uint4* vd = (uint4*)a.cache_v + ((int64_t)a.desc[r].dst_row0 + i) * row_units + unit;
+    const bool low = unit < hmask;
+    const int m0 = HALF ? (low ? unit : unit - hmask) * E : unit * P;
+    double c[N_CS], s[N_CS];
+    for (int h0 = 0; h0 < a.n_kv_heads; h0 += APPEND_UNITS_HEADS) {
+        uint4 kx[APPEND_UNITS_HEADS], vx[APPEND_UNITS_HEADS];
+#pragma unroll
+        for (int j = 0; j < APPEND_UNITS_HEADS; ++j)
+            if (h0 + j < a.n_kv_heads) {
+                kx[j] = ld_stream(ks + (h0 + j) * head_units);
+                if (a.v_new) vx[j] = ld_stream(vs + (h0 + j) * head_units);
+            }
+        if (h0 == 0) { // the loads are on their way while the angles are computed
+#pragma unroll
+            for (int p = 0; p < N_CS; ++p) sincos((double)pos * a.theta[m0 + p], &s[p], &c[p]);
+        }
+#pragma unroll
+        for (int j = 0; j < APPEND_UNITS_HEADS; ++j)
+            if (h0 + j < a.n_kv_heads) {
+                uint4 y;
+                if constexpr (HALF) y = UnitHalf<DTYPE>::rotate(kx[j], shfl_xor_u4(kx[j], hmask), low, c, s);
+                else y = Unit<DTYPE>::rotate(kx[j], c, s);
+                kd[(h0 + j) * head_units] = y;
+                if (a.v_new) vd[(h0 + j) * head_units] = vx[j]; // v_new == NULL: keys only
+            }
+    }
+}
+
 // ---- offline key rotation (Sec. 3.4 step 2): K' = R(t - cu[c]) k -------------------------------------------
 // table[pos][m] = (cos, sin)(pos * theta_m) in fp64, positions 0 .. n_pos-1
 struct ThetaArg { double v[64]; };
@@ -426,6 +477,17 @@ int tr_launch_assemble(const TrAssembleArgs& a, int dtype, int n_blocks, hipStre
 
 int tr_launch_append(const TrAppendArgs& a, int dtype, hipStream_t s)
 {
+    // many tokens: the form with 16-byte accesses (57 -> 51 us for 32768 rows of 8 heads); a request's few query tokens:
+    // one thread per pair, whose single angle is the shortest path to the first store
+    const int head_units = a.head_dim * (dtype == TR_BF16 ? 2 : 4) / 16;
+    if ((int64_t)a.total_tokens * head_units >= 65536) {
+        const int64_t n = (int64_t)a.total_tokens * head_units;
+        auto kern = dtype == TR_BF16 ? (a.rope_half ? append_units_kernel<TR_BF16, true> : append_units_kernel<TR_BF16, false>)
+                                     : (a.rope_half ? append_units_kernel<TR_F32, true> : append_units_kernel<TR_F32, false>);
+        hipLaunchKernelGGL(kern, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
+        TR_HIP(hipGetLastError());
+        return TR_OK;
+    }
     int64_t threads = (int64_t)a.total_tokens * (a.head_dim / 2);
     if (threads <= 0) return TR_OK;
     int blocks = (int)((threads + 255) / 256);

@@ -548,7 +548,14 @@ def test_offline_store_feeds_online_path(B):
                                   (synth.Shape(32, 8, 128, "bf16", 5e5, 1), (300, 17, 255), (1, 2, 0)),
                                   (synth.Shape(16, 2, 64, "bf16", 1e4), (130, 61, 77), (2, 1, 0, 2)),
                                   (synth.Shape(4, 4, 64, "f32", 1e4), (64, 40), (1, 0, 1)),
-                                  (synth.Shape(40, 20, 128, "bf16", 1e4, 1), (50, 9), (0, 1))])
+                                  (synth.Shape(40, 20, 128, "bf16", 1e4, 1), (50, 9), (0, 1)),
+                                  # launches of 4096 tokens and more take the kernel form with 16-byte accesses
+                                  (synth.QWEN2_7B, (3000, 1500, 700), (2, 0, 1, 0)),
+                                  (synth.Shape(32, 8, 128, "bf16", 5e5, 1), (2500, 2000), (1, 0)),
+                                  (synth.Shape(16, 2, 64, "bf16", 1e4), (5000, 4000), (0, 1)),
+                                  (synth.Shape(4, 4, 64, "f32", 1e4), (3000, 1500), (1, 0)),
+                                  (synth.Shape(4, 4, 64, "f32", 1e4, 1), (3000, 1500), (0, 1)),
+                                  (synth.Shape(40, 20, 128, "bf16", 1e4, 1), (2100, 2100), (0, 1))])
 def test_assemble_from_raw_keys(B, case, mode):
     sh, lens, ids = case
     rng = np.random.Generator(np.random.PCG64([123, len(lens)]))
